@@ -1,0 +1,14 @@
+"""CPU oracle for the delta-serving linear layer -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this package; the
+product path (paper_2312_05215_amd) never does, and this package never imports the product.
+
+Two independent writings of the same definition (paper Section 5.1 Eq. (2), Section 5.2):
+  * `c`  -- oracle/dz_oracle.c through ctypes: plain loops, fp32 (or fp64) accumulation in
+            ascending k; this is the oracle parity tests compare the GPU against, and the one
+            the benchmark times on the host cores;
+  * `np_` -- oracle/np_oracle.py: numpy fancy indexing + a library matmul, used to cross-check
+            the C one.
+"""
+from . import c_oracle as c          # noqa: F401
+from . import np_oracle as np_       # noqa: F401
