@@ -1,0 +1,146 @@
+/*
+ * libdz -- the per-linear-layer hot path of delta serving on one AMD MI355X (gfx950).
+ *
+ * Many fine-tuned variants of one base model are served together.  Each variant is the base weight
+ * plus a compressed delta; for one linear layer and a batch of T request rows (tokens) the layer
+ * output is
+ *
+ *     out[t] = x[t] . W_base^T  +  x[t] . Delta_{Idx[t]}^T                  (Section 5.1, Eq. (2))
+ *
+ * i.e. one fp16 GEMM over the whole batch plus a selective batched matmul (SBMM, Section 5.2) in
+ * which every row is multiplied by the delta its own request names.  A delta is 2:4 sparse along
+ * the input dimension and stored as low-bit codes on a group-wise grid (Section 4.1, steps 2-3);
+ * it is never expanded in device memory: the kernels dequantise and de-sparsify on the fly.
+ *
+ * Conventions
+ *   W, Delta : [N][K] row-major, N = output features, K = input features (torch nn.Linear layout)
+ *   x        : [T][K] fp16 row-major;  out : [T][N] fp16 row-major
+ *   fp16 buffers are passed as const void* / void*; every pointer marked DEVICE must be device
+ *   memory of the context's GPU, 16-byte aligned unless stated otherwise.
+ *   Canonical (unpacked) delta tables, the library's input format for dz_pack_delta:
+ *     codes u8 [N][K/2]  b-bit code of each kept value, two per group of four consecutive k
+ *     idx   u8 [N][K/2]  position 0..3 of each kept value in its group of four; the two positions
+ *                        of a group are distinct and ascending
+ *     scale f16[N][K/G]  grid step of the G dense columns one quantisation group spans
+ *     zero  f16[N][K/G]  integer zero-point (0 .. 2^b-1) of that grid, stored as fp16
+ *   The value stored for kept entry j of group g in row n is
+ *     (codes[n][2g+j] - zero[n][4g/G]) * scale[n][4g/G]   at column 4g + idx[n][2g+j].
+ *
+ * Shapes the kernels accept: bits in {2,4}; group in {64,128}; N % 16 == 0; K % 256 == 0;
+ * 0 <= D <= DZ_MAX_DELTAS; T >= 0 (T == 0 is a no-op).
+ *
+ * Ownership and synchronisation: the caller owns every buffer it passes.  The library owns only
+ * the workspace inside dz_ctx (segment tables, split-K partial sums, an error flag), which may grow
+ * on a call that needs more than any earlier call (that growth synchronises the stream once).
+ * Otherwise all compute entry points only enqueue work on `stream` (a hipStream_t passed as
+ * void*, NULL = the default stream) and return; nothing is synchronised except in dz_check and
+ * dz_destroy.  One dz_ctx serves one stream at a time.  x and out must not overlap.
+ *
+ * Errors: every function returns DZ_OK (0) or a negative code; nothing throws, exits or prints.
+ */
+#ifndef DZ_H
+#define DZ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DZ_OK          0
+#define DZ_ERR_ARG    (-1)  /* null pointer, negative count, D > DZ_MAX_DELTAS                      */
+#define DZ_ERR_SHAPE  (-2)  /* N, K, group outside the accepted shapes listed above                  */
+#define DZ_ERR_BITS   (-3)  /* bits not 2 or 4                                                       */
+#define DZ_ERR_ALIGN  (-4)  /* a device pointer is not 16-byte aligned                               */
+#define DZ_ERR_HIP    (-5)  /* the HIP runtime reported a failure (text from dz_last_hip_error)      */
+#define DZ_ERR_INDEX  (-6)  /* dz_check: some earlier call saw a request index outside [-1, D)       */
+
+#define DZ_MAX_DELTAS 128   /* deltas resident for one call                                          */
+
+typedef struct dz_ctx dz_ctx;
+
+/* Static text for a return code. */
+const char *dz_strerror(int rc);
+/* Text of the last HIP failure seen through this context ("" if none).  Valid until the next call. */
+const char *dz_last_hip_error(const dz_ctx *ctx);
+
+/* Create / destroy a context on GPU `device`.  dz_destroy synchronises the device. */
+int dz_create(dz_ctx **ctx, int device);
+int dz_destroy(dz_ctx *ctx);
+
+/*
+ * Size in bytes of one packed delta: the kept values' codes, their 2-bit positions (Section 4.1
+ * step 2: "non-zero values ... and their 2-bit indices"; step 3: 32/b codes per 32-bit word) and
+ * one fp16 (scale, zero) pair per row and group:
+ *     N*K*(2*bits + 4)/32  +  4*N*K/group.
+ * Returns 0 for shapes the library does not accept.
+ */
+size_t dz_packed_bytes(int N, int K, int bits, int group);
+
+/*
+ * Lay one delta's canonical tables out in the order the kernels stream them (Algorithm 1, "pack
+ * and store").  All pointers DEVICE; codes/idx need no alignment beyond 1, scale/zero 2 bytes;
+ * packed_out is caller-allocated, dz_packed_bytes() long, 16-byte aligned.  The packed layout is
+ * private to the library but position independent: the bytes may be saved, copied and reloaded.
+ * Table contents are not validated; codes are masked to `bits`, positions to 2 bits.
+ */
+int dz_pack_delta(dz_ctx *ctx, const uint8_t *codes, const uint8_t *idx, const void *scale_f16,
+                  const void *zero_f16, int N, int K, int bits, int group, void *packed_out,
+                  void *stream);
+
+/*
+ * Inverse of dz_pack_delta, for checking: any output may be NULL.  codes/idx/scale/zero reproduce
+ * the canonical tables bit for bit; dense_f32 [N][K] is the matrix the delta stands for, computed
+ * in fp32 (exact, see the value formula above).  All pointers DEVICE.
+ */
+int dz_unpack_delta(dz_ctx *ctx, const void *packed, int N, int K, int bits, int group,
+                    uint8_t *codes, uint8_t *idx, void *scale_f16, void *zero_f16,
+                    float *dense_f32, void *stream);
+
+/*
+ * Request reordering (Section 5.2, first optimisation: requests of the same delta are grouped
+ * together).  Stable counting sort of token_to_delta (DEVICE int32 [T]) over D deltas:
+ *   counts [D]   requests per delta
+ *   offsets[D+1] exclusive prefix sum; offsets[D] = number of requests that name a delta
+ *   perm   [T]   request indices, delta by delta, each delta's requests in original order;
+ *                requests with an index outside [0, D) follow at the end in original order
+ * Outputs DEVICE int32, 4-byte aligned, any may be NULL.  An index outside [-1, D) also raises
+ * the sticky error that dz_check reports.  D <= 8192 here.
+ */
+int dz_segment(dz_ctx *ctx, const int32_t *token_to_delta, int T, int D, int32_t *counts,
+               int32_t *offsets, int32_t *perm, void *stream);
+
+/* out[t] = f16( x[t] . W^T ), fp32 accumulation: the batched base product of Eq. (2). */
+int dz_base_gemm(dz_ctx *ctx, const void *x_f16, const void *W_f16, void *out_f16, int T, int N,
+                 int K, void *stream);
+
+/*
+ * SBMM (Section 5.2): for every request t with m = token_to_delta[t] in [0, D),
+ *   y[t] = x[t] . Delta_m^T  (fp32 accumulation over the kept entries),
+ * all deltas of the batch in one launch; requests with m == -1 (or out of range) get y[t] = 0.
+ *   accumulate == 0 : out[t] = f16(y[t]);   accumulate != 0 : out[t] = f16(float(out[t]) + y[t]).
+ * packed_deltas is a HOST array of D DEVICE pointers (read before the call returns), each a
+ * dz_pack_delta result for the same N, K, bits, group.  Deltas no request names are not read.
+ */
+int dz_sbmm(dz_ctx *ctx, const void *x_f16, const void *const *packed_deltas, int D,
+            const int32_t *token_to_delta, void *out_f16, int T, int N, int K, int bits, int group,
+            int accumulate, void *stream);
+
+/*
+ * Fused linear layer (Section 5.1: base and delta results are merged after each linear layer):
+ *   out[t] = f16( x[t] . W^T + x[t] . Delta_{token_to_delta[t]}^T ),
+ * both terms accumulated in fp32 and rounded to fp16 once.  Arguments as in dz_sbmm.
+ */
+int dz_linear(dz_ctx *ctx, const void *x_f16, const void *W_f16, const void *const *packed_deltas,
+              int D, const int32_t *token_to_delta, void *out_f16, int T, int N, int K, int bits,
+              int group, void *stream);
+
+/* Synchronise `stream`; return DZ_ERR_INDEX if any call since the last dz_check met a request
+ * index outside [-1, D) (that request was served with the base model only), else DZ_OK. */
+int dz_check(dz_ctx *ctx, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DZ_H */

@@ -1,7 +1,7 @@
 """CPU oracle for the delta-serving linear layer -- TEST INFRASTRUCTURE ONLY.
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import this package; the
-product path (paper_2312_05215_amd) never does, and this package never imports the product.
+product path (the HIP library and its binding) never does, and this package never imports them.
 
 Two independent writings of the same definition (paper Section 5.1 Eq. (2), Section 5.2):
   * `c`  -- oracle/dz_oracle.c through ctypes: plain loops, fp32 (or fp64) accumulation in

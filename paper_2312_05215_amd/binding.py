@@ -1,0 +1,183 @@
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+__all__ = [
+    "DZ_OK", "DZ_ERR_ARG", "DZ_ERR_SHAPE", "DZ_ERR_BITS", "DZ_ERR_ALIGN", "DZ_ERR_HIP", "DZ_ERR_INDEX",
+    "DZ_MAX_DELTAS", "DzError", "lib", "lib_path", "dz_strerror", "dz_create", "dz_destroy",
+    "dz_packed_bytes", "dz_pack_delta", "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm",
+    "dz_linear", "dz_check", "Context", "SYMBOLS",
+]
+
+DZ_OK, DZ_ERR_ARG, DZ_ERR_SHAPE, DZ_ERR_BITS, DZ_ERR_ALIGN, DZ_ERR_HIP, DZ_ERR_INDEX = 0, -1, -2, -3, -4, -5, -6
+DZ_MAX_DELTAS = 128
+
+SYMBOLS = ["dz_strerror", "dz_last_hip_error", "dz_create", "dz_destroy", "dz_packed_bytes", "dz_pack_delta",
+           "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm", "dz_linear", "dz_check"]
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_lib = None
+
+
+class DzError(RuntimeError):
+    def __init__(self, rc: int, where: str, detail: str = ""):
+        self.rc = rc
+        super().__init__(f"{where}: {dz_strerror(rc)} (rc={rc}){(' -- ' + detail) if detail else ''}")
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libdz.so")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded libdz.so.  Raises if it is missing: there is no other implementation."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} not found: build it with `python -m paper_2312_05215_amd.build` "
+                              "(or __graft_entry__.build()); libdz has no fallback path")
+        L = ctypes.CDLL(path)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        L.dz_strerror.restype = ctypes.c_char_p
+        L.dz_strerror.argtypes = [ci]
+        L.dz_last_hip_error.restype = ctypes.c_char_p
+        L.dz_last_hip_error.argtypes = [vp]
+        L.dz_create.argtypes = [ctypes.POINTER(vp), ci]
+        L.dz_destroy.argtypes = [vp]
+        L.dz_packed_bytes.restype = ctypes.c_size_t
+        L.dz_packed_bytes.argtypes = [ci, ci, ci, ci]
+        L.dz_pack_delta.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp, vp]
+        L.dz_unpack_delta.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        L.dz_segment.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp]
+        L.dz_base_gemm.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
+        L.dz_sbmm.argtypes = [vp, vp, ctypes.POINTER(vp), ci, vp, vp, ci, ci, ci, ci, ci, ci, vp]
+        L.dz_linear.argtypes = [vp, vp, vp, ctypes.POINTER(vp), ci, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.dz_check.argtypes = [vp, vp]
+        for name in SYMBOLS:
+            getattr(L, name)
+        _lib = L
+    return _lib
+
+
+def dz_strerror(rc: int) -> str:
+    return lib().dz_strerror(rc).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("libdz takes device tensors")
+    if not t.is_contiguous():
+        raise ValueError("libdz takes contiguous tensors")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def _raise(ctx, rc: int, where: str, check: bool):
+    if rc != DZ_OK and check:
+        detail = lib().dz_last_hip_error(ctx).decode() if rc == DZ_ERR_HIP and ctx else ""
+        raise DzError(rc, where, detail)
+    return rc
+
+
+def dz_create(device: int = 0) -> int:
+    h = ctypes.c_void_p()
+    rc = lib().dz_create(ctypes.byref(h), device)
+    if rc != DZ_OK:
+        raise DzError(rc, "dz_create")
+    return h.value
+
+
+def dz_destroy(ctx: int) -> int:
+    return lib().dz_destroy(ctx)
+
+
+def dz_packed_bytes(N: int, K: int, bits: int, group: int) -> int:
+    return int(lib().dz_packed_bytes(N, K, bits, group))
+
+
+def dz_pack_delta(ctx, codes, idx, scale, zero, N, K, bits, group, packed_out, stream=None, check=True) -> int:
+    rc = lib().dz_pack_delta(ctx, _ptr(codes), _ptr(idx), _ptr(scale), _ptr(zero), N, K, bits, group,
+                             _ptr(packed_out), _stream(stream))
+    return _raise(ctx, rc, "dz_pack_delta", check)
+
+
+def dz_unpack_delta(ctx, packed, N, K, bits, group, codes=None, idx=None, scale=None, zero=None, dense_f32=None,
+                    stream=None, check=True) -> int:
+    rc = lib().dz_unpack_delta(ctx, _ptr(packed), N, K, bits, group, _ptr(codes), _ptr(idx), _ptr(scale),
+                               _ptr(zero), _ptr(dense_f32), _stream(stream))
+    return _raise(ctx, rc, "dz_unpack_delta", check)
+
+
+def dz_segment(ctx, token_to_delta, T, D, counts=None, offsets=None, perm=None, stream=None, check=True) -> int:
+    rc = lib().dz_segment(ctx, _ptr(token_to_delta), T, D, _ptr(counts), _ptr(offsets), _ptr(perm), _stream(stream))
+    return _raise(ctx, rc, "dz_segment", check)
+
+
+def dz_base_gemm(ctx, x, W, out, T, N, K, stream=None, check=True) -> int:
+    rc = lib().dz_base_gemm(ctx, _ptr(x), _ptr(W), _ptr(out), T, N, K, _stream(stream))
+    return _raise(ctx, rc, "dz_base_gemm", check)
+
+
+def _ptr_array(packed_deltas: Sequence):
+    D = len(packed_deltas)
+    arr = (ctypes.c_void_p * max(D, 1))()
+    for i, p in enumerate(packed_deltas):
+        arr[i] = p if isinstance(p, int) else _ptr(p)
+    return arr, D
+
+
+def dz_sbmm(ctx, x, packed_deltas, token_to_delta, out, T, N, K, bits, group, accumulate=0, stream=None,
+            check=True) -> int:
+    arr, D = _ptr_array(packed_deltas)
+    rc = lib().dz_sbmm(ctx, _ptr(x), arr, D, _ptr(token_to_delta), _ptr(out), T, N, K, bits, group,
+                       int(accumulate), _stream(stream))
+    return _raise(ctx, rc, "dz_sbmm", check)
+
+
+def dz_linear(ctx, x, W, packed_deltas, token_to_delta, out, T, N, K, bits, group, stream=None, check=True) -> int:
+    arr, D = _ptr_array(packed_deltas)
+    rc = lib().dz_linear(ctx, _ptr(x), _ptr(W), arr, D, _ptr(token_to_delta), _ptr(out), T, N, K, bits, group,
+                         _stream(stream))
+    return _raise(ctx, rc, "dz_linear", check)
+
+
+def dz_check(ctx, stream=None) -> int:
+    return lib().dz_check(ctx, _stream(stream))
+
+
+class Context:
+    """Owns a dz_ctx handle (context manager); `.h` is the handle the dz_* functions take."""
+
+    def __init__(self, device: int = 0):
+        self.h = dz_create(device)
+
+    def close(self):
+        if self.h:
+            dz_destroy(self.h)
+            self.h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

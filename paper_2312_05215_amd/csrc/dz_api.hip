@@ -1,0 +1,299 @@
+// C ABI of libdz (include/dz.h): argument checks, the context's workspace, and dispatch to the
+// kernels.  No compute happens here.
+#include "dz_internal.h"
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int N, int K, int bits, int group, bool need_fmt)
+{
+    if (N <= 0 || K <= 0) return DZ_ERR_SHAPE;
+    if (N % 16 != 0 || K % 256 != 0) return DZ_ERR_SHAPE;
+    if (need_fmt) {
+        if (bits != 2 && bits != 4) return DZ_ERR_BITS;
+        if (group != 64 && group != 128) return DZ_ERR_SHAPE;
+    }
+    return DZ_OK;
+}
+
+int env_int(const char *name, int dflt)
+{
+    const char *s = getenv(name);
+    if (!s || !*s) return dflt;
+    return atoi(s);
+}
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+}  // namespace
+
+int dz_set_hip_error(dz_ctx *ctx, hipError_t e)
+{
+    if (e == hipSuccess) return DZ_OK;
+    if (ctx) {
+        strncpy(ctx->hip_err, hipGetErrorString(e), sizeof(ctx->hip_err) - 1);
+        ctx->hip_err[sizeof(ctx->hip_err) - 1] = 0;
+    }
+    return DZ_ERR_HIP;
+}
+
+int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st)
+{
+    if (bytes <= ctx->partial_bytes) return DZ_OK;
+    hipError_t e = hipStreamSynchronize(st);            // earlier launches may still read the old buffer
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    if (ctx->partial) (void)hipFree(ctx->partial);
+    ctx->partial = nullptr;
+    ctx->partial_bytes = 0;
+    size_t want = bytes + bytes / 4;
+    e = hipMalloc((void **)&ctx->partial, want);
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    ctx->partial_bytes = want;
+    return DZ_OK;
+}
+
+int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st)
+{
+    if (n <= ctx->counters_cap) return DZ_OK;
+    hipError_t e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    if (ctx->counters) (void)hipFree(ctx->counters);
+    ctx->counters = nullptr;
+    ctx->counters_cap = 0;
+    int want = n * 2;
+    e = hipMalloc((void **)&ctx->counters, (size_t)want * 4);
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    e = hipMemset(ctx->counters, 0, (size_t)want * 4);
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    ctx->counters_cap = want;
+    return DZ_OK;
+}
+
+static int ensure_seg(dz_ctx *ctx, int T, hipStream_t st)
+{
+    if (T <= ctx->seg_cap) return DZ_OK;
+    hipError_t e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    if (ctx->seg_perm) (void)hipFree(ctx->seg_perm);
+    if (ctx->seg_key) (void)hipFree(ctx->seg_key);
+    ctx->seg_perm = ctx->seg_key = nullptr;
+    ctx->seg_cap = 0;
+    int want = T * 2;
+    e = hipMalloc((void **)&ctx->seg_perm, (size_t)want * 4);
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    e = hipMalloc((void **)&ctx->seg_key, (size_t)want * 4);
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    ctx->seg_cap = want;
+    return DZ_OK;
+}
+
+extern "C" {
+
+const char *dz_strerror(int rc)
+{
+    switch (rc) {
+    case DZ_OK: return "ok";
+    case DZ_ERR_ARG: return "invalid argument (null pointer, negative count, or too many deltas)";
+    case DZ_ERR_SHAPE: return "unsupported shape (need N % 16 == 0, K % 256 == 0, group 64 or 128)";
+    case DZ_ERR_BITS: return "bits must be 2 or 4";
+    case DZ_ERR_ALIGN: return "device pointer is not 16-byte aligned";
+    case DZ_ERR_HIP: return "HIP runtime failure";
+    case DZ_ERR_INDEX: return "a request index was outside [-1, D)";
+    default: return "unknown error";
+    }
+}
+
+const char *dz_last_hip_error(const dz_ctx *ctx) { return ctx ? ctx->hip_err : ""; }
+
+int dz_create(dz_ctx **out, int device)
+{
+    if (!out) return DZ_ERR_ARG;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return DZ_ERR_ARG;
+    dz_ctx *ctx = new (std::nothrow) dz_ctx();
+    if (!ctx) return DZ_ERR_ARG;
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->device = device;
+    ctx->force_splits = env_int("DZ_SPLITS", 0);
+    ctx->target_wgs = env_int("DZ_TARGET_WGS", 512);
+    if (ctx->target_wgs < 1) ctx->target_wgs = 1;
+    DeviceGuard guard(device);
+    hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->err_flag, 4);
+    if (e == hipSuccess) e = hipMemset(ctx->err_flag, 0, 4);
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->seg_counts, (size_t)(DZ_SEG_MAX_D + 1) * 4);
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->seg_offsets, (size_t)(DZ_SEG_MAX_D + 2) * 4);
+    if (e == hipSuccess) {
+        ctx->seg_cap = 4096;
+        e = hipMalloc((void **)&ctx->seg_perm, (size_t)ctx->seg_cap * 4);
+        if (e == hipSuccess) e = hipMalloc((void **)&ctx->seg_key, (size_t)ctx->seg_cap * 4);
+    }
+    if (e == hipSuccess) {
+        ctx->counters_cap = 8192;
+        e = hipMalloc((void **)&ctx->counters, (size_t)ctx->counters_cap * 4);
+        if (e == hipSuccess) e = hipMemset(ctx->counters, 0, (size_t)ctx->counters_cap * 4);
+    }
+    if (e == hipSuccess) {
+        ctx->partial_bytes = (size_t)32 << 20;
+        e = hipMalloc((void **)&ctx->partial, ctx->partial_bytes);
+    }
+    if (e != hipSuccess) {
+        dz_destroy(ctx);
+        return DZ_ERR_HIP;
+    }
+    *out = ctx;
+    return DZ_OK;
+}
+
+int dz_destroy(dz_ctx *ctx)
+{
+    if (!ctx) return DZ_ERR_ARG;
+    {
+        DeviceGuard guard(ctx->device);
+        (void)hipDeviceSynchronize();
+        if (ctx->err_flag) (void)hipFree(ctx->err_flag);
+        if (ctx->seg_counts) (void)hipFree(ctx->seg_counts);
+        if (ctx->seg_offsets) (void)hipFree(ctx->seg_offsets);
+        if (ctx->seg_perm) (void)hipFree(ctx->seg_perm);
+        if (ctx->seg_key) (void)hipFree(ctx->seg_key);
+        if (ctx->counters) (void)hipFree(ctx->counters);
+        if (ctx->partial) (void)hipFree(ctx->partial);
+    }
+    delete ctx;
+    return DZ_OK;
+}
+
+size_t dz_packed_bytes(int N, int K, int bits, int group)
+{
+    if (check_shape(N, K, bits, group, true) != DZ_OK) return 0;
+    return (size_t)N * K * (2 * bits + 4) / 32 + (size_t)4 * N * K / group;
+}
+
+int dz_pack_delta(dz_ctx *ctx, const uint8_t *codes, const uint8_t *idx, const void *scale, const void *zero,
+                  int N, int K, int bits, int group, void *packed, void *stream)
+{
+    if (!ctx || !codes || !idx || !scale || !zero || !packed) return DZ_ERR_ARG;
+    int rc = check_shape(N, K, bits, group, true);
+    if (rc) return rc;
+    if (!aligned16(packed) || (reinterpret_cast<uintptr_t>(scale) & 1) || (reinterpret_cast<uintptr_t>(zero) & 1))
+        return DZ_ERR_ALIGN;
+    DeviceGuard guard(ctx->device);
+    return dz_launch_pack(ctx, codes, idx, scale, zero, N, K, bits, group, packed, (hipStream_t)stream);
+}
+
+int dz_unpack_delta(dz_ctx *ctx, const void *packed, int N, int K, int bits, int group, uint8_t *codes,
+                    uint8_t *idx, void *scale, void *zero, float *dense, void *stream)
+{
+    if (!ctx || !packed) return DZ_ERR_ARG;
+    int rc = check_shape(N, K, bits, group, true);
+    if (rc) return rc;
+    if (!aligned16(packed) || (reinterpret_cast<uintptr_t>(scale) & 1) || (reinterpret_cast<uintptr_t>(zero) & 1) ||
+        (reinterpret_cast<uintptr_t>(dense) & 3))
+        return DZ_ERR_ALIGN;
+    DeviceGuard guard(ctx->device);
+    return dz_launch_unpack(ctx, packed, N, K, bits, group, codes, idx, scale, zero, dense, (hipStream_t)stream);
+}
+
+int dz_segment(dz_ctx *ctx, const int32_t *ids, int T, int D, int32_t *counts, int32_t *offsets, int32_t *perm,
+               void *stream)
+{
+    if (!ctx || T < 0 || D < 0 || D > DZ_SEG_MAX_D || (T > 0 && !ids)) return DZ_ERR_ARG;
+    if ((reinterpret_cast<uintptr_t>(ids) | reinterpret_cast<uintptr_t>(counts) | reinterpret_cast<uintptr_t>(offsets) |
+         reinterpret_cast<uintptr_t>(perm)) & 3)
+        return DZ_ERR_ALIGN;
+    DeviceGuard guard(ctx->device);
+    // T == 0 still has to produce counts = 0 and offsets = 0: the kernel handles an empty loop
+    return dz_launch_segment(ctx, ids, T, D, counts, offsets, perm, nullptr, (hipStream_t)stream);
+}
+
+static int run_linear(dz_ctx *ctx, const void *x, const void *W, const void *const *deltas, int D,
+                      const int32_t *ids, void *out, int T, int N, int K, int bits, int group, int accumulate,
+                      bool has_base, bool has_delta, hipStream_t st)
+{
+    if (!ctx || T < 0 || D < 0 || D > DZ_MAX_DELTAS) return DZ_ERR_ARG;
+    int rc = check_shape(N, K, bits, group, has_delta);
+    if (rc) return rc;
+    if (T == 0) return DZ_OK;
+    if (!x || !out || (has_base && !W)) return DZ_ERR_ARG;
+    if (has_delta && D > 0 && (!deltas || !ids)) return DZ_ERR_ARG;
+    if (!aligned16(x) || !aligned16(out) || (has_base && !aligned16(W)) || (reinterpret_cast<uintptr_t>(ids) & 3))
+        return DZ_ERR_ALIGN;
+    DzDeltaPtrs dp;
+    memset(&dp, 0, sizeof(dp));
+    if (has_delta)
+        for (int m = 0; m < D; ++m) {
+            if (!deltas[m]) return DZ_ERR_ARG;
+            if (!aligned16(deltas[m])) return DZ_ERR_ALIGN;
+            dp.p[m] = deltas[m];
+        }
+    DeviceGuard guard(ctx->device);
+    DzStreamArgs a;
+    memset(&a, 0, sizeof(a));
+    a.x = x; a.W = W; a.out = out;
+    a.T = T; a.N = N; a.K = K; a.D = D; a.bits = bits; a.group = group;
+    a.accumulate = accumulate;
+    a.has_base = has_base;
+    // an SBMM with no deltas still runs (every request gets a zero delta term)
+    a.has_delta = has_delta && (D > 0 || !has_base);
+    if (has_delta && D > 0) {
+        rc = ensure_seg(ctx, T, st);
+        if (rc) return rc;
+        rc = dz_launch_segment(ctx, ids, T, D, nullptr, nullptr, ctx->seg_perm, ctx->seg_key, st);
+        if (rc) return rc;
+        a.perm = ctx->seg_perm;
+        a.key = ctx->seg_key;
+    }
+    return dz_launch_stream(ctx, a, dp, st);
+}
+
+int dz_base_gemm(dz_ctx *ctx, const void *x, const void *W, void *out, int T, int N, int K, void *stream)
+{
+    return run_linear(ctx, x, W, nullptr, 0, nullptr, out, T, N, K, 4, 128, 0, true, false, (hipStream_t)stream);
+}
+
+int dz_sbmm(dz_ctx *ctx, const void *x, const void *const *deltas, int D, const int32_t *ids, void *out, int T,
+            int N, int K, int bits, int group, int accumulate, void *stream)
+{
+    return run_linear(ctx, x, nullptr, deltas, D, ids, out, T, N, K, bits, group, accumulate ? 1 : 0, false, true,
+                      (hipStream_t)stream);
+}
+
+int dz_linear(dz_ctx *ctx, const void *x, const void *W, const void *const *deltas, int D, const int32_t *ids,
+              void *out, int T, int N, int K, int bits, int group, void *stream)
+{
+    return run_linear(ctx, x, W, deltas, D, ids, out, T, N, K, bits, group, 0, true, true, (hipStream_t)stream);
+}
+
+int dz_check(dz_ctx *ctx, void *stream)
+{
+    if (!ctx) return DZ_ERR_ARG;
+    DeviceGuard guard(ctx->device);
+    hipStream_t st = (hipStream_t)stream;
+    int32_t flag = 0;
+    hipError_t e = hipMemcpyAsync(&flag, ctx->err_flag, 4, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    if (flag) {
+        e = hipMemsetAsync(ctx->err_flag, 0, 4, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+        return DZ_ERR_INDEX;
+    }
+    return DZ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,156 @@
+// dz_pack_delta / dz_unpack_delta kernels: canonical tables <-> streaming layout (dz_layout.h).
+// Off the per-token path (run once per delta, Algorithm 1 "pack and store"), so these are plain
+// gather kernels: one thread per packed dword (pack) or per group of four (unpack).
+#include "dz_internal.h"
+
+namespace {
+
+// One thread builds one dword of plane C (and, for it, the matching position bits).
+// 4-bit: dword (tile, lane, step) holds 8 codes; position dword (tile, lane, h) holds 2 steps.
+// 2-bit: dword (tile, lane, c) c<2 holds 16 codes of steps 2c, 2c+1; dwords 2,3 hold positions.
+__global__ void pack_codes_kernel(DzLayout L, const uint8_t *__restrict__ codes, uint32_t *__restrict__ out)
+{
+    const size_t tiles = (size_t)L.RT * L.KT;
+    const size_t total = tiles * 64 * (L.bits == 4 ? 4 : 2);
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int per_lane = (L.bits == 4) ? 4 : 2;
+    int d = (int)(i % per_lane);
+    int lane = (int)((i / per_lane) % 64);
+    size_t tile = i / ((size_t)per_lane * 64);
+    int rt = (int)(tile / L.KT), kt = (int)(tile % L.KT);
+    int n = rt * 16 + (lane & 15), q = lane >> 4;
+    const uint8_t *row = codes + (size_t)n * (L.K / 2);
+    uint32_t w = 0;
+    const uint32_t mask = (1u << L.bits) - 1u;
+    const int nsteps = (L.bits == 4) ? 1 : 2;
+    for (int ss = 0; ss < nsteps; ++ss) {
+        int step = (L.bits == 4) ? d : 2 * d + ss;
+        int k = kt * 256 + step * 64 + q * 16;          // first dense column of this lane's step
+        for (int e = 0; e < 8; ++e) {
+            uint32_t c = row[k / 2 + e] & mask;
+            int j = e >> 1, h = e & 1;
+            int sh = (L.bits == 4) ? 16 * h + 4 * j : 16 * h + 8 * ss + 2 * j;
+            w |= c << sh;
+        }
+    }
+    out[(tile * 1024 + (size_t)lane * 16) / 4 + d] = w;
+}
+
+__global__ void pack_idx_kernel(DzLayout L, const uint8_t *__restrict__ idx, uint32_t *__restrict__ out)
+{
+    const size_t tiles = (size_t)L.RT * L.KT;
+    const size_t total = tiles * 64 * 2;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int h = (int)(i % 2);
+    int lane = (int)((i / 2) % 64);
+    size_t tile = i / 128;
+    int rt = (int)(tile / L.KT), kt = (int)(tile % L.KT);
+    int n = rt * 16 + (lane & 15), q = lane >> 4;
+    const uint8_t *row = idx + (size_t)n * (L.K / 2);
+    uint32_t w = 0;
+    for (int ss = 0; ss < 2; ++ss) {
+        int step = 2 * h + ss;
+        int k = kt * 256 + step * 64 + q * 16;
+        for (int e = 0; e < 8; ++e) w |= (uint32_t)(row[k / 2 + e] & 3u) << (16 * ss + 2 * e);
+    }
+    size_t dw = (L.bits == 4) ? (L.off_idx + tile * 512 + (size_t)lane * 8) / 4 + h
+                              : (tile * 1024 + (size_t)lane * 16) / 4 + 2 + h;
+    out[dw] = w;
+}
+
+__global__ void pack_scale_kernel(DzLayout L, const uint16_t *__restrict__ scale,
+                                  const uint16_t *__restrict__ zero, uint32_t *__restrict__ out)
+{
+    const int ng = L.K / L.group;
+    size_t total = (size_t)L.N * ng;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int n = (int)(i / ng), gq = (int)(i % ng);
+    out[dz_scale_dword(L, n, gq)] = (uint32_t)scale[i] | ((uint32_t)zero[i] << 16);
+}
+
+__device__ inline float half_bits_to_float(uint16_t h)
+{
+    _Float16 v;
+    __builtin_memcpy(&v, &h, 2);
+    return (float)v;
+}
+
+// One thread per (row, group of four): writes the two codes, two positions and, if asked, the
+// four dense fp32 values  (code - zero) * scale  (an exact product in fp32).
+__global__ void unpack_kernel(DzLayout L, const uint32_t *__restrict__ blob, uint8_t *__restrict__ codes,
+                              uint8_t *__restrict__ idx, float *__restrict__ dense)
+{
+    const int g4n = L.K / 4;
+    size_t total = (size_t)L.N * g4n;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int n = (int)(i / g4n), g4 = (int)(i % g4n);
+    const uint32_t mask = (1u << L.bits) - 1u;
+    uint32_t c[2], p[2];
+    for (int j = 0; j < 2; ++j) {
+        DzSlot s = dz_slot_of(L, n, 2 * g4 + j);
+        c[j] = (blob[dz_code_dword(L, s)] >> dz_code_shift(L, s)) & mask;
+        p[j] = (blob[dz_idx_dword(L, s)] >> dz_idx_shift(s)) & 3u;
+    }
+    size_t e = (size_t)n * (L.K / 2) + 2 * (size_t)g4;
+    if (codes) { codes[e] = (uint8_t)c[0]; codes[e + 1] = (uint8_t)c[1]; }
+    if (idx) { idx[e] = (uint8_t)p[0]; idx[e + 1] = (uint8_t)p[1]; }
+    if (dense) {
+        uint32_t sz = blob[dz_scale_dword(L, n, (4 * g4) / L.group)];
+        float s = half_bits_to_float((uint16_t)(sz & 0xffff));
+        float z = half_bits_to_float((uint16_t)(sz >> 16));
+        float a = ((float)c[0] - z) * s, b = ((float)c[1] - z) * s;
+        float *o = dense + (size_t)n * L.K + 4 * (size_t)g4;
+#pragma unroll
+        for (uint32_t pos = 0; pos < 4; ++pos) o[pos] = (p[1] == pos) ? b : (p[0] == pos) ? a : 0.f;
+    }
+}
+
+__global__ void unpack_scale_kernel(DzLayout L, const uint32_t *__restrict__ blob,
+                                    uint16_t *__restrict__ scale, uint16_t *__restrict__ zero)
+{
+    const int ng = L.K / L.group;
+    size_t total = (size_t)L.N * ng;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int n = (int)(i / ng), gq = (int)(i % ng);
+    uint32_t sz = blob[dz_scale_dword(L, n, gq)];
+    if (scale) scale[i] = (uint16_t)(sz & 0xffff);
+    if (zero) zero[i] = (uint16_t)(sz >> 16);
+}
+
+inline unsigned blocks_for(size_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
+
+}  // namespace
+
+int dz_launch_pack(dz_ctx *ctx, const uint8_t *codes, const uint8_t *idx, const void *scale,
+                   const void *zero, int N, int K, int bits, int group, void *packed, hipStream_t st)
+{
+    DzLayout L = dz_make_layout(N, K, bits, group);
+    const int bs = 256;
+    size_t tiles = (size_t)L.RT * L.KT;
+    hipLaunchKernelGGL(pack_codes_kernel, dim3(blocks_for(tiles * 64 * (bits == 4 ? 4 : 2), bs)), dim3(bs), 0,
+                       st, L, codes, (uint32_t *)packed);
+    hipLaunchKernelGGL(pack_idx_kernel, dim3(blocks_for(tiles * 128, bs)), dim3(bs), 0, st, L, idx,
+                       (uint32_t *)packed);
+    hipLaunchKernelGGL(pack_scale_kernel, dim3(blocks_for((size_t)N * (K / group), bs)), dim3(bs), 0, st, L,
+                       (const uint16_t *)scale, (const uint16_t *)zero, (uint32_t *)packed);
+    return dz_set_hip_error(ctx, hipGetLastError());
+}
+
+int dz_launch_unpack(dz_ctx *ctx, const void *packed, int N, int K, int bits, int group, uint8_t *codes,
+                     uint8_t *idx, void *scale, void *zero, float *dense, hipStream_t st)
+{
+    DzLayout L = dz_make_layout(N, K, bits, group);
+    const int bs = 256;
+    if (codes || idx || dense)
+        hipLaunchKernelGGL(unpack_kernel, dim3(blocks_for((size_t)N * (K / 4), bs)), dim3(bs), 0, st, L,
+                           (const uint32_t *)packed, codes, idx, dense);
+    if (scale || zero)
+        hipLaunchKernelGGL(unpack_scale_kernel, dim3(blocks_for((size_t)N * (K / group), bs)), dim3(bs), 0, st,
+                           L, (const uint32_t *)packed, (uint16_t *)scale, (uint16_t *)zero);
+    return dz_set_hip_error(ctx, hipGetLastError());
+}

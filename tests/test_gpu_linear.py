@@ -1,0 +1,127 @@
+"""GPU parity: dz_base_gemm, dz_sbmm and dz_linear against the CPU oracle on the same seeded inputs
+(paper Section 5.1 Eq. (2), Section 5.2).  Sizes the oracle finishes in seconds, chosen to span
+several row tiles, k tiles, column blocks, split and unsplit k, and ragged request counts."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import dz_synth as S
+from dzcase import Case, assert_close
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # name,            T,   N,    K,   D, bits, G,  ids
+    ("tiny",           8,  256,  256,  4, 4,  64, "uniform"),
+    ("b4g128_t32",    32,   96, 1024,  8, 4, 128, "uniform"),
+    ("b2g128_t64z",   64,  160, 1536, 32, 2, 128, "zipf"),
+    ("b2g64_t7",       7,   48,  768,  3, 2,  64, "uniform"),
+    ("b4g64_t1",       1,   32,  512,  2, 4,  64, "uniform"),
+    ("b4g128_t17",    17,  208,  512,  5, 4, 128, "uniform"),
+    ("b4g128_t100",  100,   64, 1024,  6, 4, 128, "uniform"),
+    ("b2g128_t200s", 200,  128,  512,  7, 2, 128, "segments"),
+    ("b4g128_t64u4",  64,  272, 2048,  4, 4, 128, "uniform"),
+]
+
+
+def _run_all(dz, c, cs, tag):
+    o = cs.out(fill=7.0)
+    dz.dz_base_gemm(c.h, cs.dx, cs.dW, o, cs.T, cs.N, cs.K)
+    assert_close(o, cs.y_base, tag + " base")
+    o = cs.out(fill=7.0)
+    dz.dz_sbmm(c.h, cs.dx, cs.packed, cs.dids, o, cs.T, cs.N, cs.K, cs.bits, cs.G, 0)
+    assert_close(o, cs.y_delta, tag + " sbmm")
+    o = cs.out(fill=7.0)
+    dz.dz_linear(c.h, cs.dx, cs.dW, cs.packed, cs.dids, o, cs.T, cs.N, cs.K, cs.bits, cs.G)
+    r = assert_close(o, cs.y, tag + " linear")
+    # accumulate: base first, then out += delta part (two roundings)
+    o2 = cs.out()
+    dz.dz_base_gemm(c.h, cs.dx, cs.dW, o2, cs.T, cs.N, cs.K)
+    dz.dz_sbmm(c.h, cs.dx, cs.packed, cs.dids, o2, cs.T, cs.N, cs.K, cs.bits, cs.G, 1)
+    assert_close(o2, cs.y, tag + " base then sbmm(accumulate)")
+    assert dz.dz_check(c.h) == dz.DZ_OK
+    return r
+
+
+@pytest.mark.parametrize("splits", ["auto", "1", "3"])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_parity_small(dz, case, splits):
+    name, T, N, K, D, bits, G, ids = case
+    print(f"case {name} splits={splits}", flush=True)
+    if splits == "auto":
+        os.environ.pop("DZ_SPLITS", None)
+    else:
+        os.environ["DZ_SPLITS"] = splits
+    try:
+        with dz.Context(0) as c:
+            cs = Case(dz, c.h, 0, T, N, K, D, bits, G, ids)
+            max_rel, mean_abs = _run_all(dz, c, cs, name)
+            print(f"  linear max_rel={max_rel:.2e} mean_abs={mean_abs:.2e}", flush=True)
+    finally:
+        os.environ.pop("DZ_SPLITS", None)
+
+
+def test_single_rounding_is_tight(dz):
+    """fp32 accumulation and one rounding: every output is within one fp16 step of the rounded
+    oracle value, and most are identical (the kernels round each dequantised delta value to fp16,
+    a 2^-11 relative perturbation of the delta term, which moves a few results across a rounding
+    boundary)."""
+    with dz.Context(0) as c:
+        cs = Case(dz, c.h, 3, 32, 96, 1024, 8, 4, 128, "uniform")
+        o = cs.out()
+        dz.dz_linear(c.h, cs.dx, cs.dW, cs.packed, cs.dids, o, cs.T, cs.N, cs.K, cs.bits, cs.G)
+        torch.cuda.synchronize()
+        ref16 = torch.from_numpy(cs.y).to(torch.float16)
+        same = (o.cpu() == ref16).float().mean().item()
+        assert same > 0.85, same
+        ulp = (o.cpu().view(torch.int16).int() - ref16.view(torch.int16).int()).abs().max().item()
+        assert ulp <= 1, ulp
+
+
+def test_base_only_requests_and_bad_indices(dz):
+    with dz.Context(0) as c:
+        T, N, K, D = 12, 64, 512, 3
+        ids = np.array([0, -1, 2, 1, -1, -1, 0, 2, 2, -1, 1, 0], np.int32)
+        cs = Case(dz, c.h, 5, T, N, K, D, 4, 128, ids)
+        _run_all(dz, c, cs, "minus-one")
+        base_rows = torch.as_tensor(ids == -1)
+        o = cs.out(fill=7.0)
+        dz.dz_sbmm(c.h, cs.dx, cs.packed, cs.dids, o, T, N, K, 4, 128, 0)
+        torch.cuda.synchronize()
+        assert (o.cpu()[base_rows] == 0).all()
+        # all requests base-only
+        cs2 = Case(dz, c.h, 6, 5, N, K, D, 4, 128, np.full(5, -1, np.int32))
+        _run_all(dz, c, cs2, "all-base")
+        # an index outside [-1, D): served base-only, reported by dz_check
+        bad = ids.copy(); bad[3] = 3; bad[7] = -2
+        cs3 = Case(dz, c.h, 5, T, N, K, D, 4, 128, bad)
+        o = cs3.out()
+        dz.dz_linear(c.h, cs3.dx, cs3.dW, cs3.packed, cs3.dids, o, T, N, K, 4, 128)
+        assert_close(o, cs3.y, "bad ids")          # the oracle treats them as base-only too
+        assert dz.dz_check(c.h) == dz.DZ_ERR_INDEX
+        assert dz.dz_check(c.h) == dz.DZ_OK
+
+
+def test_degenerate_calls(dz):
+    with dz.Context(0) as c:
+        cs = Case(dz, c.h, 7, 4, 32, 256, 2, 4, 64, "uniform")
+        o = cs.out(fill=3.0)
+        # T == 0: nothing happens
+        assert dz.dz_linear(c.h, cs.dx, cs.dW, cs.packed, cs.dids, o, 0, cs.N, cs.K, 4, 64) == dz.DZ_OK
+        torch.cuda.synchronize()
+        assert (o == 3.0).all()
+        # D == 0: the base product alone; SBMM gives zeros
+        dz.dz_linear(c.h, cs.dx, cs.dW, [], cs.dids, o, cs.T, cs.N, cs.K, 4, 64)
+        assert_close(o, cs.y_base, "D=0 linear")
+        dz.dz_sbmm(c.h, cs.dx, [], cs.dids, o, cs.T, cs.N, cs.K, 4, 64, 0)
+        torch.cuda.synchronize()
+        assert (o == 0).all()
+        # argument errors
+        assert dz.dz_linear(c.h, cs.dx, cs.dW, cs.packed, cs.dids, o, cs.T, cs.N, 200, 4, 64, check=False) == dz.DZ_ERR_SHAPE
+        assert dz.dz_linear(c.h, cs.dx, cs.dW, cs.packed, cs.dids, o, cs.T, cs.N, cs.K, 3, 64, check=False) == dz.DZ_ERR_BITS
+        assert dz.dz_linear(c.h, cs.dx, None, cs.packed, cs.dids, o, cs.T, cs.N, cs.K, 4, 64, check=False) == dz.DZ_ERR_ARG
+        assert dz.dz_linear(c.h, cs.dx, cs.dW, cs.packed * 65, cs.dids, o, cs.T, cs.N, cs.K, 4, 64, check=False) == dz.DZ_ERR_ARG
+        assert dz.dz_base_gemm(c.h, cs.dx.view(-1)[1:], cs.dW, o, 1, cs.N, cs.K, check=False) == dz.DZ_ERR_ALIGN
+        assert dz.dz_check(c.h) == dz.DZ_OK
