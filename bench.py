@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark: decode throughput of the base-GEMM + SBMM linear layers on one MI355X.
+
+Workload (`7b_decode`): a Llama-7B-shaped stack of linear projections per transformer layer --
+q,k,v,o 4096x4096, gate,up 11008x4096, down 4096x11008, fp16 base ~N(0,0.02) -- with 8 resident
+deltas (4-bit codes, 2:4 sparse, group 128) and a decode batch of 32 request rows whose delta ids
+are uniform over the 8 deltas.  One *step* is one pass over all linear projections of all 32
+layers (224 fused dz_linear calls: request reordering, base product, SBMM, merge), every layer
+with its own weights and deltas resident in HBM (about 34 GB, far beyond the 256 MB last-level
+cache).  Attention, norms, embeddings and sampling are not part of the path.  Inputs are seeded
+and synthetic; no file is read.
+
+Prints ONE JSON line; see the design doc for how each field is derived.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="7b_decode", choices=["7b_decode", "7b_decode_many", "tiny"])
+    ap.add_argument("--layers", type=int, default=0, help="distinct resident layers (0 = all of the model)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import dz_synth as S
+    import paper_2312_05215_amd as dz
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    cfg = S.config(args.workload)
+    n_layers = args.layers if args.layers > 0 else cfg.layers
+    projs = S.projections_of(cfg)
+    ctx = dz.Context(0)
+    nbytes = {(N, K): dz.dz_packed_bytes(N, K, cfg.bits, cfg.group) for _, N, K in projs}
+
+    ids = cfg.make_ids(S.stream(args.seed, cfg.name, "ids"))
+    n_active = int(ids.unique().numel())
+    d_ids = ids.to(dev)
+
+    t0 = time.time()
+    layers = []          # per layer: list of (N, K, W, [packed], x, out)
+    host_layer0 = None   # canonical tables of layer 0 for the CPU baseline
+    for l in range(n_layers):
+        row = []
+        keep = []
+        for name, N, K in projs:
+            p = S.make_projection(cfg, args.seed, l, name, N, K, device=dev)
+            packed = []
+            for t in p.tabs:
+                buf = torch.empty(nbytes[(N, K)], dtype=torch.uint8, device=dev)
+                dz.dz_pack_delta(ctx.h, t.codes, t.idx, t.scale, t.zero, N, K, cfg.bits, cfg.group, buf)
+                packed.append(buf)
+            out = torch.empty(cfg.T, N, dtype=torch.float16, device=dev)
+            row.append((N, K, p.W, packed, p.x, out))
+            if l == 0 and not args.no_cpu_baseline:
+                keep.append((name, N, K, p.W.cpu(), [t.to("cpu") for t in p.tabs], p.x.cpu()))
+            del p
+        if l == 0:
+            host_layer0 = keep
+        layers.append(row)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    def step():
+        for row in layers:
+            for N, K, W, packed, x, out in row:
+                dz.dz_linear(ctx.h, x, W, packed, d_ids, out, cfg.T, N, K, cfg.bits, cfg.group)
+
+    for _ in range(args.warmup):
+        step()
+    assert dz.dz_check(ctx.h) == dz.DZ_OK
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_total = ev0.elapsed_time(ev1)
+    ms_per_step = ms_total / args.steps
+    assert dz.dz_check(ctx.h) == dz.DZ_OK
+
+    # a model pass over the cfg.layers layers: scale if fewer distinct layers were made resident
+    ms_model = ms_per_step * cfg.layers / n_layers
+    tokens_per_s = cfg.T / (ms_model * 1e-3)
+
+    launches_per_step = n_layers * len(projs)
+    bytes_per_step = n_layers * sum(S.algorithmic_bytes(N, K, cfg.T, cfg.bits, cfg.group, n_active) for _, N, K in projs)
+    avg_launch_us = ms_per_step * 1e3 / launches_per_step
+    achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "stream_kernel (fused base GEMM + SBMM)", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch_avg": bytes_per_step // launches_per_step,
+                "avg_launch_us": round(avg_launch_us, 2), "launches_per_step": launches_per_step}
+
+    cpu = None
+    if not args.no_cpu_baseline and host_layer0:
+        import numpy as np
+        import oracle
+        idn = ids.numpy()
+        t1 = time.time()
+        for name, N, K, W, tabs, x in host_layer0:
+            dense = [oracle.c.dequant(t.codes.numpy(), t.idx.numpy(), t.scale.numpy(), t.zero.numpy(), cfg.bits, cfg.group)
+                     for t in tabs]
+            oracle.c.linear(x.numpy(), W.numpy(), dense, idn)
+            del dense
+        cpu_s = time.time() - t1
+        cpu = {"value": round(cfg.T / (cpu_s * cfg.layers), 4), "unit": "tokens/s", "cores": oracle.c.num_threads(),
+               "kind": "oracle",
+               "sample": f"layer 0 of {cfg.layers} (all {len(projs)} projections, dense dequantisation of {cfg.D} deltas "
+                         f"+ per-request dot products) took {cpu_s:.1f} s; value extrapolates x{cfg.layers} layers"}
+
+    line = {
+        "metric": "SBMM+base decode tokens/s and achieved HBM GB/s (% of peak) per layer",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": cfg.layers, "resident_layers": n_layers, "tokens": cfg.T,
+                   "deltas": cfg.D, "active_deltas": n_active, "bits": cfg.bits, "group": cfg.group,
+                   "projections_per_layer": len(projs), "gen_seconds": round(gen_s, 1)},
+        "hbm_gbs": round(achieved, 1), "hbm_frac_of_peak": round(achieved / HBM_PEAK_GBS, 4),
+        "us_per_layer": round(ms_per_step * 1e3 / n_layers, 2),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

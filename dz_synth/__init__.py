@@ -223,3 +223,45 @@ CONFIGS: Dict[str, Config] = {
 
 def config(name: str) -> Config:
     return CONFIGS[name]
+
+
+# ------------------------------------------------------------------- whole projections of a config
+@dataclass
+class Projection:
+    """Inputs of one linear layer of a config: base weight, D delta tables, activations."""
+    name: str
+    N: int
+    K: int
+    W: torch.Tensor
+    tabs: List[DeltaTables]
+    x: torch.Tensor
+
+
+def projections_of(cfg: Config) -> List[Tuple[str, int, int]]:
+    """(name, N, K) of every linear projection of one transformer layer, in execution order."""
+    out = []
+    for s in cfg.shapes:
+        for i in range(s.count):
+            out.append((f"{s.name}{i}", s.N, s.K))
+    return out
+
+
+def make_projection(cfg: Config, seed: int, layer: int, name: str, N: int, K: int,
+                    device: str = "cpu", with_tables: bool = True) -> Projection:
+    """All tensors of one projection, each from its own sub-stream keyed by
+    (config, layer, projection, tensor kind, delta id)."""
+    key = (cfg.name, layer, name)
+    W = make_base(N, K, stream(seed, *key, "W", device=device), cfg.base_std)
+    x = make_x(cfg.T, K, stream(seed, *key, "x", device=device))
+    tabs = []
+    if with_tables:
+        tabs = [make_delta_tables(N, K, cfg.bits, cfg.group, stream(seed, *key, "delta", m, device=device),
+                                  std=cfg.delta_std) for m in range(cfg.D)]
+    return Projection(name, N, K, W, tabs, x)
+
+
+def algorithmic_bytes(N: int, K: int, T: int, bits: int, group: int, n_active: int) -> int:
+    """Bytes one fused linear call must move at least: the base weight, the packed deltas that
+    have at least one request, x, out and the index vector."""
+    packed = N * K * (2 * bits + 4) // 32 + 4 * N * K // group
+    return 2 * N * K + n_active * packed + 2 * T * K + 2 * T * N + 4 * T

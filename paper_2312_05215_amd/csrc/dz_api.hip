@@ -131,6 +131,8 @@ int dz_create(dz_ctx **out, int device)
     ctx->force_splits = env_int("DZ_SPLITS", 0);
     ctx->target_wgs = env_int("DZ_TARGET_WGS", 512);
     if (ctx->target_wgs < 1) ctx->target_wgs = 1;
+    ctx->fix_mode = env_int("DZ_FIX_MODE", 2);
+    ctx->round_tiles = env_int("DZ_ROUND_TILES", 0);
     DeviceGuard guard(device);
     hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->err_flag, 4);
@@ -249,7 +251,11 @@ static int run_linear(dz_ctx *ctx, const void *x, const void *W, const void *con
     a.has_base = has_base;
     // an SBMM with no deltas still runs (every request gets a zero delta term)
     a.has_delta = has_delta && (D > 0 || !has_base);
-    if (has_delta && D > 0) {
+    a.err_flag = ctx->err_flag;
+    a.fix_mode = ctx->fix_mode;
+    if (has_delta && D > 0 && T <= 64) {
+        a.ids = ids;                    // small batches are sorted inside the streaming kernel
+    } else if (has_delta && D > 0) {
         rc = ensure_seg(ctx, T, st);
         if (rc) return rc;
         rc = dz_launch_segment(ctx, ids, T, D, nullptr, nullptr, ctx->seg_perm, ctx->seg_key, st);

@@ -23,6 +23,8 @@ struct dz_ctx {
     // tuning knobs (environment overrides, read once)
     int force_splits;       // DZ_SPLITS
     int target_wgs;         // DZ_TARGET_WGS
+    int fix_mode;           // DZ_FIX_MODE
+    int round_tiles;        // DZ_ROUND_TILES
 };
 
 #define DZ_SEG_MAX_D 8192
@@ -36,6 +38,9 @@ struct DzStreamArgs {
     void *out;                  // [T][N] fp16
     const int32_t *perm;        // sorted request order or null (identity)
     const int32_t *key;         // delta of each sorted position or null (no deltas)
+    const int32_t *ids;         // raw request->delta indices: the kernel sorts them itself (T <= 64)
+    int32_t *err_flag;
+    int fix_mode;               // how split-k partials are made visible: 1 fences, 2 agent-scope accesses
     float *partial;
     int32_t *counters;
     int T, N, K, D, bits, group;

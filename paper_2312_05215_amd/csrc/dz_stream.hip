@@ -114,114 +114,217 @@ __device__ __forceinline__ h16 load_b(const _Float16 *xs, const Geo &g, int j, i
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
 }
 
-template <int R, int J>
-__device__ __forceinline__ void base_pass(const _Float16 *__restrict__ W, int K, const int (&rtc)[R], int kr0,
-                                          int kr1, const _Float16 *xs, const Geo &g, f4 (&acc)[R][J])
+__device__ __forceinline__ h8 as_h8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
 {
-    for (int kt = kr0; kt < kr1; ++kt) {
-        h8 aw[R][4][2];
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    return __builtin_bit_cast(h8, (u4){a, b, c, d});
+}
+
+// The work of a workgroup inside one LDS round is a flat list of *tasks*, each a fixed-size load
+// per lane and row tile followed by MFMAs against the x slice in LDS:
+//   base task  (kt, step): 32 bytes of W      -> two dense MFMAs per (row tile, column block)
+//   delta task (segment, kt): one packed tile -> four sparse MFMAs per (row tile, column block)
+// Tasks are software-pipelined: the loads of task t + P - 1 are issued before task t is computed.
+struct Cursor {
+    int delta;      // 0: base tasks, 1: delta tasks
+    int kt;         // k tile
+    int sub;        // base: step 0..3; delta: segment number
+};
+
+template <int BITS, int GROUP, bool HB>
+struct Fmt {
+    static constexpr int GPT = 256 / GROUP;                         // quantisation groups per tile row
+    static constexpr int SC0 = (BITS == 4) ? 6 : 4;                 // first scale dword in a stage
+    static constexpr int NDW = SC0 + GPT;
+    static constexpr int SD = (NDW < 8) ? 8 : NDW;                  // dwords per lane and row tile
+};
+
+// Per-lane byte offsets that never change during the kernel; every task's addresses are a
+// wave-uniform base plus one of these.
+struct LaneOffs {
+    uint32_t w;         // row * K * 2 + q * 16      (W fragment of a base step)
+    uint32_t c;         // lane * 16                 (packed codes)
+    uint32_t i;         // lane * 8                  (packed positions, 4-bit layout)
+    uint32_t s;         // row * GPT * 4             (scale/zero pairs)
+};
+
+// Streaming loads go through buffer instructions: a wave-uniform resource (base pointer + size in
+// bytes, checked by the hardware), a wave-uniform byte offset in an SGPR and a per-lane byte
+// offset that never changes.  Nothing else in the pipeline touches the vector-memory counter.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+// Every task issues the same load instructions per row tile -- 16, 8, 8 bytes (and 8 more for the
+// 4-bit / group-64 format) -- whatever its kind; only resource and offsets differ.  That keeps the
+// issue path free of branches around loads, so the load counter the compiler waits on is exact
+// and the loads of the next two tasks really stay in flight while a task computes.
+//   base step : W bytes 0-15, 64-71, 72-79 of the lane's two 16-byte fragments
+//   4-bit tile: codes, positions, scales        2-bit tile: codes+positions, scales, (scales again)
+template <int BITS, int GROUP, int R, int SD, bool HB, bool HD>
+__device__ __forceinline__ void issue_task(const Cursor &c, const DzStreamArgs &a, const Geo &g, const int (&rtc)[R],
+                                           const LaneOffs &lo, const unsigned long long *s_seg_blob, uint32_t off_idx,
+                                           uint32_t off_scale, uint32_t blob_bytes, uint32_t w_bytes,
+                                           uint32_t (&st)[R][SD])
+{
+    typedef Fmt<BITS, GROUP, HB> F;
+    bool is_base;
+    if constexpr (!HD) is_base = true;
+    else if constexpr (!HB) is_base = false;
+    else is_base = !c.delta;
+    const void *base = a.W;
+    uint32_t bytes = w_bytes;
+    uint32_t v0 = lo.w, v1 = lo.w, v2 = lo.w;
+    if constexpr (HD) {
+        if (!is_base) {
+            const unsigned long long bp = s_seg_blob[c.sub];
+            const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)bp);
+            const uint32_t h = __builtin_amdgcn_readfirstlane((uint32_t)(bp >> 32));
+            base = (const void *)(((unsigned long long)h << 32) | l);
+            bytes = blob_bytes;
+            v0 = lo.c; v1 = (BITS == 4) ? lo.i : lo.s; v2 = lo.s;
+        }
+    }
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(base, bytes);
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const _Float16 *wp = W + (size_t)(rtc[r] * 16 + g.row) * K + (size_t)kt * 256 + 8 * g.q;
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                aw[r][st][0] = *(const h8 *)(wp + st * 64);
-                aw[r][st][1] = *(const h8 *)(wp + st * 64 + 32);
+    for (int r = 0; r < R; ++r) {
+        uint32_t o0 = 0, o1 = 0, o2 = 0, o3 = 0;
+        if constexpr (HB) {
+            o0 = ((uint32_t)rtc[r] * 16u * (uint32_t)a.K + (uint32_t)c.kt * 256u + (uint32_t)c.sub * 64u) * 2u;
+            o1 = o0 + 64u; o2 = o0 + 72u; o3 = o0;
+        }
+        if constexpr (HD) {
+            if (!is_base) {
+                const uint32_t tile = (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)c.kt;
+                const uint32_t sc = off_scale + tile * (16u * F::GPT * 4u);
+                o0 = tile * 1024u;
+                o1 = (BITS == 4) ? off_idx + tile * 512u : sc;
+                o2 = (BITS == 4) ? sc : ((F::GPT == 4) ? sc + 8u : sc);
+                o3 = sc + 8u;
             }
         }
+        const u32x4 x0 = __builtin_amdgcn_raw_buffer_load_b128(rs, v0, o0, 0);
+        const u32x2 x1 = __builtin_amdgcn_raw_buffer_load_b64(rs, v1, o1, 0);
+        const u32x2 x2 = __builtin_amdgcn_raw_buffer_load_b64(rs, v2, o2, 0);
+        st[r][0] = x0.x; st[r][1] = x0.y; st[r][2] = x0.z; st[r][3] = x0.w;
+        st[r][4] = x1.x; st[r][5] = x1.y; st[r][6] = x2.x; st[r][7] = x2.y;
+        if constexpr (SD > 8) {       // 4-bit, group 64: four scale dwords
+            const u32x2 x3 = __builtin_amdgcn_raw_buffer_load_b64(rs, v2, o3, 0);
+            st[r][8] = x3.x; st[r][9] = x3.y;
+        }
+    }
+}
+
+template <int R, int J, int SD>
+__device__ __forceinline__ void compute_base(const uint32_t (&st)[R][SD], const _Float16 *xs, const Geo &g, int kofs,
+                                             f4 (&acc)[R][J])
+{
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
+    for (int j = 0; j < J; ++j) {
+        const h16 b = load_b(xs, g, j, kofs);
+        const h8 b0 = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, 6, 7);
+        const h8 b1 = __builtin_shufflevector(b, b, 8, 9, 10, 11, 12, 13, 14, 15);
 #pragma unroll
-            for (int j = 0; j < J; ++j) {
-                h16 b = load_b(xs, g, j, (kt - kr0) * 256 + st * 64);
-                h8 b0 = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, 6, 7);
-                h8 b1 = __builtin_shufflevector(b, b, 8, 9, 10, 11, 12, 13, 14, 15);
+        for (int r = 0; r < R; ++r) {
+            const h8 a0 = as_h8(st[r][0], st[r][1], st[r][2], st[r][3]);
+            const h8 a1 = as_h8(st[r][4], st[r][5], st[r][6], st[r][7]);
+            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0, acc[r][j], 0, 0, 0);
+            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1, acc[r][j], 0, 0, 0);
+        }
+    }
+}
+
+// The four steps of one packed tile against column blocks j0 .. j0 + C - 1.
+template <int BITS, int GROUP, int R, int J, int SD, int C, bool HB>
+__device__ __forceinline__ void compute_delta(const uint32_t (&st)[R][SD], const _Float16 *xs, const Geo &g, int kofs,
+                                              int j0, f4 (&tmp)[R][J])
+{
+    typedef Fmt<BITS, GROUP, HB> F;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        h8 av[R];
+        uint32_t idxw[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const h2 sz2 = as_h2(st[r][F::SC0 + s * F::GPT / 4]);
+            const h2 s2 = (h2){sz2.x, sz2.x};
+            const h2 z2 = (h2){sz2.y, sz2.y};
+            uint32_t w;
+            if (BITS == 4) { w = st[r][s]; idxw[r] = st[r][4 + (s >> 1)]; }
+            else { w = st[r][s >> 1] >> (8 * (s & 1)); idxw[r] = st[r][2 + (s >> 1)]; }
+            av[r] = dequant_step<BITS>(w, s2, z2);
+        }
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const h16 b = load_b(xs, g, j0 + c, kofs + s * 64);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (s & 1) tmp[r][c] = smfmac<1>(av[r], b, tmp[r][c], (int)idxw[r]);
+                else tmp[r][c] = smfmac<0>(av[r], b, tmp[r][c], (int)idxw[r]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);      // keep one step's operands live at a time
+    }
+}
+
+template <int BITS, int GROUP, int R, int J, int SD, bool HB, bool HD>
+__device__ __forceinline__ void compute_task(const Cursor &c, int kr0, int kr1, const uint32_t (&st)[R][SD],
+                                             const _Float16 *xs, const Geo &g, const int *s_seg_begin,
+                                             f4 (&acc)[R][J], f4 (&tmp)[R][J])
+{
+    bool is_base = false;
+    if constexpr (HB) {
+        is_base = !c.delta;
+        if (is_base) compute_base<R, J, SD>(st, xs, g, (c.kt - kr0) * 256 + c.sub * 64, acc);
+    }
+    if constexpr (HD) if (!is_base) {
+        const int sb = __builtin_amdgcn_readfirstlane(s_seg_begin[c.sub]);
+        const int se = __builtin_amdgcn_readfirstlane(s_seg_begin[c.sub + 1]);
+        const int j0 = sb >> 4;
+        const int C = ((se - 1) >> 4) - j0 + 1;
+        if (c.kt == kr0) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int j = 0; j < J; ++j) tmp[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
+        }
+        const int kofs = (c.kt - kr0) * 256;
+        if (C == 1) compute_delta<BITS, GROUP, R, J, SD, 1, HB>(st, xs, g, kofs, j0, tmp);
+        else if (J >= 2 && C == 2) compute_delta<BITS, GROUP, R, J, SD, (J >= 2 ? 2 : 1), HB>(st, xs, g, kofs, j0, tmp);
+        else if (J >= 3 && C == 3) compute_delta<BITS, GROUP, R, J, SD, (J >= 3 ? 3 : 1), HB>(st, xs, g, kofs, j0, tmp);
+        else if (J >= 4 && C == 4) compute_delta<BITS, GROUP, R, J, SD, (J >= 4 ? 4 : 1), HB>(st, xs, g, kofs, j0, tmp);
+        if (c.kt == kr1 - 1) {
+            // merge: only the columns (sorted positions) that belong to this segment
+#pragma unroll
+            for (int cc = 0; cc < J; ++cc) {
+                const int pos = 16 * (j0 + cc) + g.row;
+                const bool in = cc < C && pos >= sb && pos < se;
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aw[r][st][0], b0, acc[r][j], 0, 0, 0);
-                    acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aw[r][st][1], b1, acc[r][j], 0, 0, 0);
+                    f4 t = tmp[r][cc];
+                    if (!in) t = (f4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int j = 0; j < J; ++j)
+                        if (j == j0 + cc) acc[r][j] += t;
                 }
             }
         }
     }
 }
 
-// One delta's contribution for the sorted positions [sb, se) of this chunk, which overlap column
-// blocks j0 .. j0 + C - 1.
-template <int BITS, int GROUP, int R, int J, int C>
-__device__ __forceinline__ void delta_pass(const uint8_t *__restrict__ blob, size_t off_idx, size_t off_scale,
-                                           const int (&rtc)[R], int kr0, int kr1, const _Float16 *xs,
-                                           const Geo &g, int j0, int sb, int se, f4 (&acc)[R][J])
+__device__ __forceinline__ void advance(Cursor &c, int kr0, int kr1, bool has_base)
 {
-    constexpr int GPT = 256 / GROUP;            // quantisation groups per tile row (2 or 4)
-    f4 tmp[R][C];
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int c = 0; c < C; ++c) tmp[r][c] = (f4){0.f, 0.f, 0.f, 0.f};
-
-    for (int kt = kr0; kt < kr1; ++kt) {
-        uint32_t cw[R][4];      // 4-bit: dword per step; 2-bit: [0],[1] hold two steps each
-        uint32_t iw[R][2];
-        uint32_t sz[R][GPT];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const size_t tile = (size_t)rtc[r] * g.KT + kt;
-            const uint4 v = *(const uint4 *)(blob + tile * 1024 + (size_t)g.lane * 16);
-            if (BITS == 4) {
-                cw[r][0] = v.x; cw[r][1] = v.y; cw[r][2] = v.z; cw[r][3] = v.w;
-                const uint2 iv = *(const uint2 *)(blob + off_idx + tile * 512 + (size_t)g.lane * 8);
-                iw[r][0] = iv.x; iw[r][1] = iv.y;
-            } else {
-                cw[r][0] = v.x; cw[r][1] = v.y; cw[r][2] = 0; cw[r][3] = 0;
-                iw[r][0] = v.z; iw[r][1] = v.w;
-            }
-            const uint8_t *sp = blob + off_scale + tile * (16 * GPT * 4) + (size_t)g.row * (GPT * 4);
-            if (GPT == 2) {
-                const uint2 s = *(const uint2 *)sp;
-                sz[r][0] = s.x; sz[r][1] = s.y;
-            } else {
-                const uint4 s = *(const uint4 *)sp;
-                sz[r][0] = s.x; sz[r][1] = s.y; sz[r][GPT - 2] = s.z; sz[r][GPT - 1] = s.w;
-            }
+    if (has_base && !c.delta) {
+        if (++c.sub == 4) {
+            c.sub = 0;
+            if (++c.kt == kr1) { c.delta = 1; c.kt = kr0; c.sub = 0; }
         }
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            h16 b[C];
-#pragma unroll
-            for (int c = 0; c < C; ++c) b[c] = load_b(xs, g, j0 + c, (kt - kr0) * 256 + st * 64);
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const uint32_t szw = sz[r][st * GPT / 4];
-                const h2 sz2 = as_h2(szw);
-                const h2 s2 = (h2){sz2.x, sz2.x};
-                const h2 z2 = (h2){sz2.y, sz2.y};
-                uint32_t w;
-                if (BITS == 4) w = cw[r][st];
-                else w = cw[r][st >> 1] >> (8 * (st & 1));
-                const h8 a = dequant_step<BITS>(w, s2, z2);
-                const int idxw = (int)iw[r][st >> 1];
-#pragma unroll
-                for (int c = 0; c < C; ++c) {
-                    if (st & 1) tmp[r][c] = smfmac<1>(a, b[c], tmp[r][c], idxw);
-                    else tmp[r][c] = smfmac<0>(a, b[c], tmp[r][c], idxw);
-                }
-            }
-        }
-    }
-    // merge: only the columns (sorted positions) that belong to this segment
-#pragma unroll
-    for (int c = 0; c < C; ++c) {
-        const int pos = 16 * (j0 + c) + g.row;
-        const bool in = pos >= sb && pos < se;
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            f4 t = tmp[r][c];
-            if (!in) t = (f4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int j = 0; j < J; ++j)
-                if (j == j0 + c) acc[r][j] += t;
-        }
+    } else {
+        if (++c.kt == kr1) { c.kt = kr0; ++c.sub; }
     }
 }
 
@@ -236,13 +339,19 @@ __device__ __forceinline__ void store_row4(_Float16 *p, f4 v, int accumulate)
     *(h4 *)p = r;
 }
 
+
 template <int BITS, int GROUP, int R, int J, bool HAS_BASE, bool HAS_DELTA>
-__global__ __launch_bounds__(THREADS) void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
-                                                         size_t off_idx, size_t off_scale)
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 4))) void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
+                                                         size_t off_idx, size_t off_scale, size_t blob_total)
 {
+    typedef Fmt<BITS, GROUP, HAS_BASE> F;
+    constexpr int SD = F::SD;
     extern __shared__ __attribute__((aligned(16))) _Float16 xs[];     // [16J][LDW]
-    __shared__ int s_tok[64];
-    __shared__ int s_seg_delta[64];
+    __shared__ int s_tok[64];               // request row of each sorted position (-1: none)
+    __shared__ int s_key[64];               // delta of each sorted position
+    __shared__ int s_raw[64];
+    __shared__ int s_rank[64];
+    __shared__ unsigned long long s_seg_blob[64];
     __shared__ int s_seg_begin[65];
     __shared__ int s_nseg;
     __shared__ int s_last;
@@ -252,7 +361,12 @@ __global__ __launch_bounds__(THREADS) void stream_kernel(DzStreamArgs a, DzDelta
     g.lane = tid & 63; g.row = g.lane & 15; g.q = g.lane >> 4;
     g.KT = a.K >> 8;
     g.LDW = round_tiles * 256 + LDS_PAD;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    LaneOffs lo;
+    lo.w = (uint32_t)g.row * (uint32_t)a.K * 2u + (uint32_t)g.q * 16u;
+    lo.c = (uint32_t)g.lane * 16u;
+    lo.i = (uint32_t)g.lane * 8u;
+    lo.s = (uint32_t)g.row * (uint32_t)(F::GPT * 4);
 
     int unit = blockIdx.x;
     const int ks = unit % a.S; unit /= a.S;
@@ -264,30 +378,67 @@ __global__ __launch_bounds__(THREADS) void stream_kernel(DzStreamArgs a, DzDelta
     const int cnt = min(64, a.T - p0);
     const int RT = a.N >> 4;
 
-    // ---- this chunk's rows and delta segments (sorted order comes from the segment pass)
-    if (tid < 64) {
+    // ---- sorted order of this chunk's request rows (paper Section 5.2: requests of one delta are
+    // grouped).  Up to 64 rows are ranked here by every workgroup from the raw index vector (rank =
+    // rows with a smaller delta + earlier rows with the same delta), which saves a launch and a
+    // dependent load; larger batches read the order a segment pass left in the workspace.
+    if (HAS_DELTA && a.ids) {
+        if (tid < 64) {
+            int key = INT_MAX;
+            if (tid < cnt) {
+                const int id = a.ids[tid];
+                const bool valid = id >= 0 && id < a.D;
+                key = valid ? id : a.D;
+                if (!valid && id != -1 && blockIdx.x == 0) atomicOr(a.err_flag, 1);
+            }
+            s_raw[tid] = key;
+            s_rank[tid] = 0;
+        }
+        __syncthreads();
+        {
+            const int t = tid & 63, part = tid >> 6;
+            const int kme = s_raw[t];
+            int c = 0;
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                const int j = part * 16 + jj;
+                const int kj = s_raw[j];
+                c += (kj < kme || (kj == kme && j < t)) ? 1 : 0;
+            }
+            atomicAdd(&s_rank[t], c);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            const int r = s_rank[tid];
+            s_tok[r] = tid < cnt ? tid : -1;
+            s_key[r] = s_raw[tid];
+        }
+    } else if (tid < 64) {
         int tok = -1, key = INT_MAX;
         if (tid < cnt) {
             tok = a.perm ? a.perm[p0 + tid] : p0 + tid;
             if (HAS_DELTA && a.key) key = a.key[p0 + tid];
         }
         s_tok[tid] = tok;
-        if (HAS_DELTA) {
-            const bool valid = key >= 0 && key < a.D;
-            const int prev = __shfl_up(key, 1, 64);
-            const bool start = valid && (tid == 0 || prev != key);
-            const unsigned long long sm = __ballot(start);
-            const unsigned long long vm = __ballot(valid);
-            if (start) {
-                const int i = (int)lanes_below(sm);
-                s_seg_delta[i] = key;
-                s_seg_begin[i] = tid;
-            }
-            if (tid == 0) {
-                const int ns = __builtin_popcountll(sm);
-                s_nseg = ns;
-                s_seg_begin[ns] = __builtin_popcountll(vm);     // valid rows are a prefix of the chunk
-            }
+        s_key[tid] = key;
+    }
+    __syncthreads();
+    if (HAS_DELTA && tid < 64) {
+        const int key = s_key[tid];
+        const int prev = tid ? s_key[tid - 1] : -1;
+        const bool valid = key >= 0 && key < a.D;
+        const bool start = valid && (tid == 0 || prev != key);
+        const unsigned long long sm = __ballot(start);
+        const unsigned long long vm = __ballot(valid);
+        if (start) {
+            const int i = (int)lanes_below(sm);
+            s_seg_blob[i] = (unsigned long long)dp.p[key];
+            s_seg_begin[i] = tid;
+        }
+        if (tid == 0) {
+            const int ns = __builtin_popcountll(sm);
+            s_nseg = ns;
+            s_seg_begin[ns] = __builtin_popcountll(vm);     // rows that name a delta are a prefix
         }
     }
 
@@ -300,16 +451,21 @@ __global__ __launch_bounds__(THREADS) void stream_kernel(DzStreamArgs a, DzDelta
         rtc[r] = rvalid[r] ? rt : RT - 1;
     }
 
-    f4 acc[R][J];
+    f4 acc[R][J], tmp[R][J];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int j = 0; j < J; ++j) acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < J; ++j) {
+            acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
+            tmp[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
+        }
 
     const _Float16 *x = (const _Float16 *)a.x;
+    const uint32_t w_bytes = (uint32_t)a.N * (uint32_t)a.K * 2u;
+    const uint32_t blob_bytes = (uint32_t)blob_total;
     for (int kr0 = kt0; kr0 < kt1; kr0 += round_tiles) {
         const int kr1 = min(kt1, kr0 + round_tiles);
-        __syncthreads();                         // s_tok visible; previous round's readers done
+        __syncthreads();                         // tables visible; previous round's LDS readers done
         // ---- x[:, k-slice of this round] -> LDS, rows in sorted order, rows past cnt zero
         const int cpr = (kr1 - kr0) * 32;        // 16-byte pieces per row
         for (int i = tid; i < 16 * J * cpr; i += THREADS) {
@@ -321,27 +477,43 @@ __global__ __launch_bounds__(THREADS) void stream_kernel(DzStreamArgs a, DzDelta
         }
         __syncthreads();
 
-        if (HAS_BASE) base_pass<R, J>((const _Float16 *)a.W, a.K, rtc, kr0, kr1, xs, g, acc);
-
-        if (HAS_DELTA) {
-            const int nseg = s_nseg;
-            for (int si = 0; si < nseg; ++si) {
-                const int m = __builtin_amdgcn_readfirstlane(s_seg_delta[si]);
-                const int sb = __builtin_amdgcn_readfirstlane(s_seg_begin[si]);
-                const int se = __builtin_amdgcn_readfirstlane(s_seg_begin[si + 1]);
-                const int j0 = sb >> 4;
-                const int C = ((se - 1) >> 4) - j0 + 1;
-                const uint8_t *blob = (const uint8_t *)dp.p[m];
-                if (C == 1)
-                    delta_pass<BITS, GROUP, R, J, 1>(blob, off_idx, off_scale, rtc, kr0, kr1, xs, g, j0, sb, se, acc);
-                else if (J >= 2 && C == 2)
-                    delta_pass<BITS, GROUP, R, J, (J >= 2 ? 2 : 1)>(blob, off_idx, off_scale, rtc, kr0, kr1, xs, g, j0, sb, se, acc);
-                else if (J >= 3 && C == 3)
-                    delta_pass<BITS, GROUP, R, J, (J >= 3 ? 3 : 1)>(blob, off_idx, off_scale, rtc, kr0, kr1, xs, g, j0, sb, se, acc);
-                else if (J >= 4 && C == 4)
-                    delta_pass<BITS, GROUP, R, J, (J >= 4 ? 4 : 1)>(blob, off_idx, off_scale, rtc, kr0, kr1, xs, g, j0, sb, se, acc);
+        const int ntr = kr1 - kr0;
+        const int nseg = HAS_DELTA ? s_nseg : 0;
+        const int total = (HAS_BASE ? 4 * ntr : 0) + nseg * ntr;
+        Cursor ci, cc;
+        ci.delta = HAS_BASE ? 0 : 1; ci.kt = kr0; ci.sub = 0;
+        cc = ci;
+        // three stage buffers as separate named arrays (so each stays in registers), rotated by hand.
+        // The issue cursor stops at the last task and re-issues it (a few redundant cache hits at
+        // the end of a round) so that issuing needs no branch.
+        uint32_t st0[R][SD], st1[R][SD], st2[R][SD];
+        int ti = 0, tc = 0;
+#define DZ_ISSUE(buf)                                                                                              \
+    do {                                                                                                           \
+        issue_task<BITS, GROUP, R, SD, HAS_BASE, HAS_DELTA>(ci, a, g, rtc, lo, s_seg_blob, (uint32_t)off_idx,        \
+                                                            (uint32_t)off_scale, blob_bytes, w_bytes, buf); \
+        if (++ti < total) advance(ci, kr0, kr1, HAS_BASE);                                                         \
+    } while (0)
+#define DZ_STEP(cur, nxt)                                                                                          \
+    do {                                                                                                           \
+        DZ_ISSUE(nxt);                                                                                             \
+        if (tc < total) {                                                                                          \
+            compute_task<BITS, GROUP, R, J, SD, HAS_BASE, HAS_DELTA>(cc, kr0, kr1, cur, xs, g, s_seg_begin, acc, tmp); \
+            advance(cc, kr0, kr1, HAS_BASE);                                                                       \
+        }                                                                                                          \
+        ++tc;                                                                                                      \
+    } while (0)
+        if (total > 0) {
+            DZ_ISSUE(st0);
+            DZ_ISSUE(st1);
+            while (tc < total) {
+                DZ_STEP(st0, st2);
+                DZ_STEP(st1, st0);
+                DZ_STEP(st2, st1);
             }
         }
+#undef DZ_ISSUE
+#undef DZ_STEP
     }
 
     // ---- results: lane 16q + c holds rows 4q..4q+3 of the row tile for request column c
@@ -359,6 +531,10 @@ __global__ __launch_bounds__(THREADS) void stream_kernel(DzStreamArgs a, DzDelta
         return;
     }
 
+    // ---- split k: partial tiles meet in fp32.  Partials are written and later read with
+    // agent-scope accesses (coherent across the chip's L2s without flushing them); each wave
+    // waits for its stores to complete before the barrier, then one thread bumps the arrival
+    // counter of the row block.  The last workgroup to arrive adds the slices in fixed order.
     const int Tp = ((a.T + 63) >> 6) << 6;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -366,22 +542,33 @@ __global__ __launch_bounds__(THREADS) void stream_kernel(DzStreamArgs a, DzDelta
 #pragma unroll
         for (int j = 0; j < J; ++j) {
             const int pr = 16 * j + g.row;
-            if (pr < cnt)
-                *(f4 *)(a.partial + ((size_t)ks * Tp + p0 + pr) * a.N + rtc[r] * 16 + 4 * g.q) = acc[r][j];
+            if (pr < cnt) {
+                float *p = a.partial + ((size_t)ks * Tp + p0 + pr) * a.N + rtc[r] * 16 + 4 * g.q;
+                if (a.fix_mode == 2) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        __hip_atomic_store(p + i, acc[r][j][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    *(f4 *)p = acc[r][j];
+                }
+            }
         }
     }
-    __threadfence();
+    __builtin_amdgcn_s_waitcnt(0);               // this wave's stores have completed
     __syncthreads();
     if (tid == 0) {
         int32_t *ctr = a.counters + chunk * NRB + rb;
-        const int old = atomicAdd(ctr, 1);
+        if (a.fix_mode != 2) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int last = (old == a.S - 1);
-        if (last) *ctr = 0;                      // ready for the next launch
+        if (last) {
+            __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+            if (a.fix_mode != 2) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        }
         s_last = last;
     }
     __syncthreads();
     if (!s_last) return;
-    __threadfence();
     const int width = WAVES * R * 16;            // rows of N per row block
     const int nq = width / 4;
     for (int i = tid; i < cnt * nq; i += THREADS) {
@@ -389,8 +576,16 @@ __global__ __launch_bounds__(THREADS) void stream_kernel(DzStreamArgs a, DzDelta
         const int n = rb * width + c4 * 4;
         if (n >= a.N) continue;
         f4 sum = (f4){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < a.S; ++s)
-            sum += *(const f4 *)(a.partial + ((size_t)s * Tp + p0 + pr) * a.N + n);
+        for (int s = 0; s < a.S; ++s) {
+            const float *p = a.partial + ((size_t)s * Tp + p0 + pr) * a.N + n;
+            if (a.fix_mode == 2) {
+#pragma unroll
+                for (int i2 = 0; i2 < 4; ++i2)
+                    sum[i2] += __hip_atomic_load(p + i2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                sum += *(const f4 *)p;
+            }
+        }
         const int tok = s_tok[pr];
         store_row4(out + (size_t)tok * a.N + n, sum, a.accumulate);
     }
@@ -407,7 +602,7 @@ hipError_t launch_one(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(k, dim3(grid), dim3(THREADS), lds, st, a, dp, NRB, round_tiles, L.off_idx, L.off_scale);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(THREADS), lds, st, a, dp, NRB, round_tiles, L.off_idx, L.off_scale, L.total);
     return hipGetLastError();
 }
 
@@ -455,7 +650,7 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &d
     const size_t Tp = (size_t)nchunks * 64;
     // keep the partial-sum workspace modest
     while (S > 1 && (size_t)S * Tp * a.N * 4 > ((size_t)256 << 20)) --S;
-    int round_tiles = 2;
+    int round_tiles = ctx->round_tiles > 0 ? ctx->round_tiles : (J <= 2 ? 4 : 2);
     const int max_slice = (KT + S - 1) / S;
     if (round_tiles > max_slice) round_tiles = max_slice;
     const size_t lds = (size_t)16 * J * (round_tiles * 256 + LDS_PAD) * sizeof(_Float16);
@@ -470,6 +665,7 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &d
     a.counters = ctx->counters;
     const long long grid = units0 * S;
     if (grid > 0x7fffffffLL) return DZ_ERR_SHAPE;
+    if ((unsigned long long)a.N * a.K * 2ull >= (1ull << 32)) return DZ_ERR_SHAPE;     // 32-bit byte offsets
     DzLayout L = dz_make_layout(a.N, a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
     hipError_t e;
     if (a.has_base && a.has_delta)
