@@ -131,7 +131,8 @@ int dz_create(dz_ctx **out, int device)
     ctx->force_splits = env_int("DZ_SPLITS", 0);
     ctx->target_wgs = env_int("DZ_TARGET_WGS", 512);
     if (ctx->target_wgs < 1) ctx->target_wgs = 1;
-    ctx->fix_mode = env_int("DZ_FIX_MODE", 2);
+    ctx->wg_waves = env_int("DZ_WAVES", 8);
+    ctx->wg_rtiles = env_int("DZ_RTILES", 1);
     ctx->round_tiles = env_int("DZ_ROUND_TILES", 0);
     DeviceGuard guard(device);
     hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
@@ -252,7 +253,10 @@ static int run_linear(dz_ctx *ctx, const void *x, const void *W, const void *con
     // an SBMM with no deltas still runs (every request gets a zero delta term)
     a.has_delta = has_delta && (D > 0 || !has_base);
     a.err_flag = ctx->err_flag;
-    a.fix_mode = ctx->fix_mode;
+#ifdef DZ_PROF
+    if (!ctx->prof) (void)hipMalloc((void **)&ctx->prof, (size_t)1 << 24);
+    a.prof = ctx->prof;
+#endif
     if (has_delta && D > 0 && T <= 64) {
         a.ids = ids;                    // small batches are sorted inside the streaming kernel
     } else if (has_delta && D > 0) {
@@ -283,6 +287,13 @@ int dz_linear(dz_ctx *ctx, const void *x, const void *W, const void *const *delt
 {
     return run_linear(ctx, x, W, deltas, D, ids, out, T, N, K, bits, group, 0, true, true, (hipStream_t)stream);
 }
+
+#ifdef DZ_PROF
+int dz_prof_read(dz_ctx *ctx, void *host, size_t bytes)
+{
+    return hipMemcpy(host, ctx->prof, bytes, hipMemcpyDeviceToHost) == hipSuccess ? 0 : -5;
+}
+#endif
 
 int dz_check(dz_ctx *ctx, void *stream)
 {

@@ -23,8 +23,11 @@ struct dz_ctx {
     // tuning knobs (environment overrides, read once)
     int force_splits;       // DZ_SPLITS
     int target_wgs;         // DZ_TARGET_WGS
-    int fix_mode;           // DZ_FIX_MODE
     int round_tiles;        // DZ_ROUND_TILES
+    int wg_waves, wg_rtiles; // DZ_WAVES, DZ_RTILES: workgroup shape of the streaming kernel
+#ifdef DZ_PROF
+    long long *prof;
+#endif
 };
 
 #define DZ_SEG_MAX_D 8192
@@ -40,7 +43,9 @@ struct DzStreamArgs {
     const int32_t *key;         // delta of each sorted position or null (no deltas)
     const int32_t *ids;         // raw request->delta indices: the kernel sorts them itself (T <= 64)
     int32_t *err_flag;
-    int fix_mode;               // how split-k partials are made visible: 1 fences, 2 agent-scope accesses
+#ifdef DZ_PROF
+    long long *prof;            // 8 timestamps per workgroup (development builds only)
+#endif
     float *partial;
     int32_t *counters;
     int T, N, K, D, bits, group;

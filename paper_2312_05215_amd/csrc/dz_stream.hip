@@ -38,8 +38,6 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h16 __attribute__((ext_vector_type(16)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-constexpr int WAVES = 4;
-constexpr int THREADS = WAVES * 64;
 constexpr int LDS_PAD = 8;          // halfs of padding per LDS row (keeps 16-byte reads off one bank set)
 
 __device__ inline unsigned lanes_below(unsigned long long m)
@@ -120,27 +118,22 @@ __device__ __forceinline__ h8 as_h8(uint32_t a, uint32_t b, uint32_t c, uint32_t
     return __builtin_bit_cast(h8, (u4){a, b, c, d});
 }
 
-// The work of a workgroup inside one LDS round is a flat list of *tasks*, each a fixed-size load
-// per lane and row tile followed by MFMAs against the x slice in LDS:
-//   base task  (kt, step): 32 bytes of W      -> two dense MFMAs per (row tile, column block)
-//   delta task (segment, kt): one packed tile -> four sparse MFMAs per (row tile, column block)
-// Tasks are software-pipelined: the loads of task t + P - 1 are issued before task t is computed.
-struct Cursor {
-    int delta;      // 0: base tasks, 1: delta tasks
-    int kt;         // k tile
-    int sub;        // base: step 0..3; delta: segment number
-};
-
-template <int BITS, int GROUP, bool HB>
+// Inside one LDS round (a slice of k whose x rows sit in LDS) a wave first streams its rows of W
+// (base phase), then the packed tiles of every delta that has requests (delta phase).  Both phases
+// are software pipelines over fixed-size loads held in named register buffers:
+//   base step  : 2 x 16 bytes of W per lane and row tile  -> two dense MFMAs per column block
+//   delta task : one packed tile (16 rows x 256 k)         -> four sparse MFMAs per column block
+// Loads go through buffer instructions: a wave-uniform resource (base pointer + size in bytes,
+// bounds-checked by the hardware), a wave-uniform byte offset in an SGPR and a per-lane byte
+// offset that never changes.  No branch surrounds a streaming load, so the hardware load counter
+// the compiler waits on is exact and the prefetched loads really stay in flight.
+template <int BITS, int GROUP>
 struct Fmt {
     static constexpr int GPT = 256 / GROUP;                         // quantisation groups per tile row
     static constexpr int SC0 = (BITS == 4) ? 6 : 4;                 // first scale dword in a stage
-    static constexpr int NDW = SC0 + GPT;
-    static constexpr int SD = (NDW < 8) ? 8 : NDW;                  // dwords per lane and row tile
+    static constexpr int SD = SC0 + GPT;                            // dwords per lane and row tile
 };
 
-// Per-lane byte offsets that never change during the kernel; every task's addresses are a
-// wave-uniform base plus one of these.
 struct LaneOffs {
     uint32_t w;         // row * K * 2 + q * 16      (W fragment of a base step)
     uint32_t c;         // lane * 16                 (packed codes)
@@ -148,9 +141,6 @@ struct LaneOffs {
     uint32_t s;         // row * GPT * 4             (scale/zero pairs)
 };
 
-// Streaming loads go through buffer instructions: a wave-uniform resource (base pointer + size in
-// bytes, checked by the hardware), a wave-uniform byte offset in an SGPR and a per-lane byte
-// offset that never changes.  Nothing else in the pipeline touches the vector-memory counter.
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
@@ -159,68 +149,22 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
 
-// Every task issues the same load instructions per row tile -- 16, 8, 8 bytes (and 8 more for the
-// 4-bit / group-64 format) -- whatever its kind; only resource and offsets differ.  That keeps the
-// issue path free of branches around loads, so the load counter the compiler waits on is exact
-// and the loads of the next two tasks really stay in flight while a task computes.
-//   base step : W bytes 0-15, 64-71, 72-79 of the lane's two 16-byte fragments
-//   4-bit tile: codes, positions, scales        2-bit tile: codes+positions, scales, (scales again)
-template <int BITS, int GROUP, int R, int SD, bool HB, bool HD>
-__device__ __forceinline__ void issue_task(const Cursor &c, const DzStreamArgs &a, const Geo &g, const int (&rtc)[R],
-                                           const LaneOffs &lo, const unsigned long long *s_seg_blob, uint32_t off_idx,
-                                           uint32_t off_scale, uint32_t blob_bytes, uint32_t w_bytes,
-                                           uint32_t (&st)[R][SD])
+// ------------------------------------------------------------------------------------ base phase
+// One step = 64 k of W for R row tiles.  step index s counts from the start of the round.
+template <int R>
+__device__ __forceinline__ void base_issue(__amdgpu_buffer_rsrc_t rw, const uint32_t (&wbase)[R], uint32_t voff, int s,
+                                           u32x4 (&buf)[R][2])
 {
-    typedef Fmt<BITS, GROUP, HB> F;
-    bool is_base;
-    if constexpr (!HD) is_base = true;
-    else if constexpr (!HB) is_base = false;
-    else is_base = !c.delta;
-    const void *base = a.W;
-    uint32_t bytes = w_bytes;
-    uint32_t v0 = lo.w, v1 = lo.w, v2 = lo.w;
-    if constexpr (HD) {
-        if (!is_base) {
-            const unsigned long long bp = s_seg_blob[c.sub];
-            const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)bp);
-            const uint32_t h = __builtin_amdgcn_readfirstlane((uint32_t)(bp >> 32));
-            base = (const void *)(((unsigned long long)h << 32) | l);
-            bytes = blob_bytes;
-            v0 = lo.c; v1 = (BITS == 4) ? lo.i : lo.s; v2 = lo.s;
-        }
-    }
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(base, bytes);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        uint32_t o0 = 0, o1 = 0, o2 = 0, o3 = 0;
-        if constexpr (HB) {
-            o0 = ((uint32_t)rtc[r] * 16u * (uint32_t)a.K + (uint32_t)c.kt * 256u + (uint32_t)c.sub * 64u) * 2u;
-            o1 = o0 + 64u; o2 = o0 + 72u; o3 = o0;
-        }
-        if constexpr (HD) {
-            if (!is_base) {
-                const uint32_t tile = (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)c.kt;
-                const uint32_t sc = off_scale + tile * (16u * F::GPT * 4u);
-                o0 = tile * 1024u;
-                o1 = (BITS == 4) ? off_idx + tile * 512u : sc;
-                o2 = (BITS == 4) ? sc : ((F::GPT == 4) ? sc + 8u : sc);
-                o3 = sc + 8u;
-            }
-        }
-        const u32x4 x0 = __builtin_amdgcn_raw_buffer_load_b128(rs, v0, o0, 0);
-        const u32x2 x1 = __builtin_amdgcn_raw_buffer_load_b64(rs, v1, o1, 0);
-        const u32x2 x2 = __builtin_amdgcn_raw_buffer_load_b64(rs, v2, o2, 0);
-        st[r][0] = x0.x; st[r][1] = x0.y; st[r][2] = x0.z; st[r][3] = x0.w;
-        st[r][4] = x1.x; st[r][5] = x1.y; st[r][6] = x2.x; st[r][7] = x2.y;
-        if constexpr (SD > 8) {       // 4-bit, group 64: four scale dwords
-            const u32x2 x3 = __builtin_amdgcn_raw_buffer_load_b64(rs, v2, o3, 0);
-            st[r][8] = x3.x; st[r][9] = x3.y;
-        }
+        const uint32_t o = wbase[r] + (uint32_t)s * 128u;
+        buf[r][0] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, o, 0);
+        buf[r][1] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, o + 64u, 0);
     }
 }
 
-template <int R, int J, int SD>
-__device__ __forceinline__ void compute_base(const uint32_t (&st)[R][SD], const _Float16 *xs, const Geo &g, int kofs,
+template <int R, int J>
+__device__ __forceinline__ void base_compute(const u32x4 (&buf)[R][2], const _Float16 *xs, const Geo &g, int kofs,
                                              f4 (&acc)[R][J])
 {
 #pragma unroll
@@ -230,20 +174,55 @@ __device__ __forceinline__ void compute_base(const uint32_t (&st)[R][SD], const 
         const h8 b1 = __builtin_shufflevector(b, b, 8, 9, 10, 11, 12, 13, 14, 15);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const h8 a0 = as_h8(st[r][0], st[r][1], st[r][2], st[r][3]);
-            const h8 a1 = as_h8(st[r][4], st[r][5], st[r][6], st[r][7]);
-            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0, acc[r][j], 0, 0, 0);
-            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1, acc[r][j], 0, 0, 0);
+            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, buf[r][0]), b0, acc[r][j], 0, 0, 0);
+            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, buf[r][1]), b1, acc[r][j], 0, 0, 0);
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------------- delta phase
+struct Cursor {
+    int kt;         // k tile
+    int seg;        // segment number
+};
+
+template <int BITS, int GROUP, int R>
+__device__ __forceinline__ void delta_issue(const Cursor &c, const Geo &g, const int (&rtc)[R], const LaneOffs &lo,
+                                            const unsigned long long *s_seg_blob, uint32_t off_idx,
+                                            uint32_t off_scale, uint32_t blob_bytes,
+                                            uint32_t (&st)[R][Fmt<BITS, GROUP>::SD])
+{
+    typedef Fmt<BITS, GROUP> F;
+    const unsigned long long bp = s_seg_blob[c.seg];
+    const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)bp);
+    const uint32_t h = __builtin_amdgcn_readfirstlane((uint32_t)(bp >> 32));
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc((const void *)(((unsigned long long)h << 32) | l), blob_bytes);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t tile = (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)c.kt;
+        const uint32_t sc = off_scale + tile * (16u * F::GPT * 4u);
+        const u32x4 x0 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.c, tile * 1024u, 0);
+        st[r][0] = x0.x; st[r][1] = x0.y; st[r][2] = x0.z; st[r][3] = x0.w;
+        if constexpr (BITS == 4) {
+            const u32x2 x1 = __builtin_amdgcn_raw_buffer_load_b64(rs, lo.i, off_idx + tile * 512u, 0);
+            st[r][4] = x1.x; st[r][5] = x1.y;
+        }
+        if constexpr (F::GPT == 2) {
+            const u32x2 x2 = __builtin_amdgcn_raw_buffer_load_b64(rs, lo.s, sc, 0);
+            st[r][F::SC0] = x2.x; st[r][F::SC0 + 1] = x2.y;
+        } else {
+            const u32x4 x2 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.s, sc, 0);
+            st[r][F::SC0] = x2.x; st[r][F::SC0 + 1] = x2.y; st[r][F::SC0 + 2] = x2.z; st[r][F::SC0 + 3] = x2.w;
         }
     }
 }
 
 // The four steps of one packed tile against column blocks j0 .. j0 + C - 1.
-template <int BITS, int GROUP, int R, int J, int SD, int C, bool HB>
-__device__ __forceinline__ void compute_delta(const uint32_t (&st)[R][SD], const _Float16 *xs, const Geo &g, int kofs,
-                                              int j0, f4 (&tmp)[R][J])
+template <int BITS, int GROUP, int R, int J, int C>
+__device__ __forceinline__ void delta_steps(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], const _Float16 *xs,
+                                            const Geo &g, int kofs, int j0, f4 (&tmp)[R][J])
 {
-    typedef Fmt<BITS, GROUP, HB> F;
+    typedef Fmt<BITS, GROUP> F;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         h8 av[R];
@@ -271,61 +250,47 @@ __device__ __forceinline__ void compute_delta(const uint32_t (&st)[R][SD], const
     }
 }
 
-template <int BITS, int GROUP, int R, int J, int SD, bool HB, bool HD>
-__device__ __forceinline__ void compute_task(const Cursor &c, int kr0, int kr1, const uint32_t (&st)[R][SD],
-                                             const _Float16 *xs, const Geo &g, const int *s_seg_begin,
-                                             f4 (&acc)[R][J], f4 (&tmp)[R][J])
+template <int BITS, int GROUP, int R, int J>
+__device__ __forceinline__ void delta_compute(const Cursor &c, int kr0, int kr1,
+                                              const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], const _Float16 *xs,
+                                              const Geo &g, const int *s_seg_begin, f4 (&acc)[R][J], f4 (&tmp)[R][J])
 {
-    bool is_base = false;
-    if constexpr (HB) {
-        is_base = !c.delta;
-        if (is_base) compute_base<R, J, SD>(st, xs, g, (c.kt - kr0) * 256 + c.sub * 64, acc);
+    const int sb = __builtin_amdgcn_readfirstlane(s_seg_begin[c.seg]);
+    const int se = __builtin_amdgcn_readfirstlane(s_seg_begin[c.seg + 1]);
+    const int j0 = sb >> 4;
+    const int C = ((se - 1) >> 4) - j0 + 1;
+    if (c.kt == kr0) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int j = 0; j < J; ++j) tmp[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
     }
-    if constexpr (HD) if (!is_base) {
-        const int sb = __builtin_amdgcn_readfirstlane(s_seg_begin[c.sub]);
-        const int se = __builtin_amdgcn_readfirstlane(s_seg_begin[c.sub + 1]);
-        const int j0 = sb >> 4;
-        const int C = ((se - 1) >> 4) - j0 + 1;
-        if (c.kt == kr0) {
+    const int kofs = (c.kt - kr0) * 256;
+    if (C == 1) delta_steps<BITS, GROUP, R, J, 1>(st, xs, g, kofs, j0, tmp);
+    else if (J >= 2 && C == 2) delta_steps<BITS, GROUP, R, J, (J >= 2 ? 2 : 1)>(st, xs, g, kofs, j0, tmp);
+    else if (J >= 3 && C == 3) delta_steps<BITS, GROUP, R, J, (J >= 3 ? 3 : 1)>(st, xs, g, kofs, j0, tmp);
+    else if (J >= 4 && C == 4) delta_steps<BITS, GROUP, R, J, (J >= 4 ? 4 : 1)>(st, xs, g, kofs, j0, tmp);
+    if (c.kt == kr1 - 1) {
+        // merge: only the columns (sorted positions) that belong to this segment
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+        for (int cc = 0; cc < J; ++cc) {
+            const int pos = 16 * (j0 + cc) + g.row;
+            const bool in = cc < C && pos >= sb && pos < se;
 #pragma unroll
-                for (int j = 0; j < J; ++j) tmp[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
-        }
-        const int kofs = (c.kt - kr0) * 256;
-        if (C == 1) compute_delta<BITS, GROUP, R, J, SD, 1, HB>(st, xs, g, kofs, j0, tmp);
-        else if (J >= 2 && C == 2) compute_delta<BITS, GROUP, R, J, SD, (J >= 2 ? 2 : 1), HB>(st, xs, g, kofs, j0, tmp);
-        else if (J >= 3 && C == 3) compute_delta<BITS, GROUP, R, J, SD, (J >= 3 ? 3 : 1), HB>(st, xs, g, kofs, j0, tmp);
-        else if (J >= 4 && C == 4) compute_delta<BITS, GROUP, R, J, SD, (J >= 4 ? 4 : 1), HB>(st, xs, g, kofs, j0, tmp);
-        if (c.kt == kr1 - 1) {
-            // merge: only the columns (sorted positions) that belong to this segment
+            for (int r = 0; r < R; ++r) {
+                f4 t = tmp[r][cc];
+                if (!in) t = (f4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int cc = 0; cc < J; ++cc) {
-                const int pos = 16 * (j0 + cc) + g.row;
-                const bool in = cc < C && pos >= sb && pos < se;
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    f4 t = tmp[r][cc];
-                    if (!in) t = (f4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int j = 0; j < J; ++j)
-                        if (j == j0 + cc) acc[r][j] += t;
-                }
+                for (int j = 0; j < J; ++j)
+                    if (j == j0 + cc) acc[r][j] += t;
             }
         }
     }
 }
 
-__device__ __forceinline__ void advance(Cursor &c, int kr0, int kr1, bool has_base)
+__device__ __forceinline__ void advance(Cursor &c, int kr0, int kr1)
 {
-    if (has_base && !c.delta) {
-        if (++c.sub == 4) {
-            c.sub = 0;
-            if (++c.kt == kr1) { c.delta = 1; c.kt = kr0; c.sub = 0; }
-        }
-    } else {
-        if (++c.kt == kr1) { c.kt = kr0; ++c.sub; }
-    }
+    if (++c.kt == kr1) { c.kt = kr0; ++c.seg; }
 }
 
 __device__ __forceinline__ void store_row4(_Float16 *p, f4 v, int accumulate)
@@ -340,12 +305,14 @@ __device__ __forceinline__ void store_row4(_Float16 *p, f4 v, int accumulate)
 }
 
 
-template <int BITS, int GROUP, int R, int J, bool HAS_BASE, bool HAS_DELTA>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 4))) void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
-                                                         size_t off_idx, size_t off_scale, size_t blob_total)
+
+template <int BITS, int GROUP, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
+__global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
+                                                            size_t off_idx, size_t off_scale, size_t blob_total)
 {
-    typedef Fmt<BITS, GROUP, HAS_BASE> F;
+    typedef Fmt<BITS, GROUP> F;
     constexpr int SD = F::SD;
+    constexpr int THREADS = WAVES * 64;
     extern __shared__ __attribute__((aligned(16))) _Float16 xs[];     // [16J][LDW]
     __shared__ int s_tok[64];               // request row of each sorted position (-1: none)
     __shared__ int s_key[64];               // delta of each sorted position
@@ -357,6 +324,12 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 4)))
     __shared__ int s_last;
 
     const int tid = threadIdx.x;
+#ifdef DZ_PROF
+#define DZ_T(i) do { if (tid == 0) a.prof[(size_t)blockIdx.x * 8 + (i)] = (long long)wall_clock64(); } while (0)
+#else
+#define DZ_T(i) do { } while (0)
+#endif
+    DZ_T(0);
     Geo g;
     g.lane = tid & 63; g.row = g.lane & 15; g.q = g.lane >> 4;
     g.KT = a.K >> 8;
@@ -396,12 +369,13 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 4)))
         }
         __syncthreads();
         {
+            constexpr int PER = 64 / WAVES;     // each wave compares against its share of the rows
             const int t = tid & 63, part = tid >> 6;
             const int kme = s_raw[t];
             int c = 0;
 #pragma unroll
-            for (int jj = 0; jj < 16; ++jj) {
-                const int j = part * 16 + jj;
+            for (int jj = 0; jj < PER; ++jj) {
+                const int j = part * PER + jj;
                 const int kj = s_raw[j];
                 c += (kj < kme || (kj == kme && j < t)) ? 1 : 0;
             }
@@ -441,6 +415,8 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 4)))
             s_seg_begin[ns] = __builtin_popcountll(vm);     // rows that name a delta are a prefix
         }
     }
+    __syncthreads();
+    DZ_T(1);
 
     int rtc[R];
     bool rvalid[R];
@@ -463,50 +439,98 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 4)))
     const _Float16 *x = (const _Float16 *)a.x;
     const uint32_t w_bytes = (uint32_t)a.N * (uint32_t)a.K * 2u;
     const uint32_t blob_bytes = (uint32_t)blob_total;
+    const int nseg = HAS_DELTA ? s_nseg : 0;
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.W ? a.W : a.x, HAS_BASE ? w_bytes : 0u);
     for (int kr0 = kt0; kr0 < kt1; kr0 += round_tiles) {
         const int kr1 = min(kt1, kr0 + round_tiles);
-        __syncthreads();                         // tables visible; previous round's LDS readers done
-        // ---- x[:, k-slice of this round] -> LDS, rows in sorted order, rows past cnt zero
-        const int cpr = (kr1 - kr0) * 32;        // 16-byte pieces per row
-        for (int i = tid; i < 16 * J * cpr; i += THREADS) {
-            const int rr = i / cpr, cc = i - rr * cpr;
-            const int tok = s_tok[rr];
-            uint4 v = {0u, 0u, 0u, 0u};
-            if (tok >= 0) v = *(const uint4 *)(x + (size_t)tok * a.K + (size_t)kr0 * 256 + cc * 8);
-            *(uint4 *)(xs + rr * g.LDW + cc * 8) = v;
-        }
-        __syncthreads();
-
         const int ntr = kr1 - kr0;
-        const int nseg = HAS_DELTA ? s_nseg : 0;
-        const int total = (HAS_BASE ? 4 * ntr : 0) + nseg * ntr;
+        const int nd = nseg * ntr;               // delta tasks of this round
+        const int nsteps = 4 * ntr;              // base steps of this round
         Cursor ci, cc;
-        ci.delta = HAS_BASE ? 0 : 1; ci.kt = kr0; ci.sub = 0;
+        ci.kt = kr0; ci.seg = 0;
         cc = ci;
-        // three stage buffers as separate named arrays (so each stays in registers), rotated by hand.
-        // The issue cursor stops at the last task and re-issues it (a few redundant cache hits at
-        // the end of a round) so that issuing needs no branch.
+        // named stage buffers (so each stays in registers), rotated by hand.  Issue cursors stop at
+        // the last task / step and re-issue it (a few redundant cache hits at the end of a round)
+        // so that issuing needs no branch.
         uint32_t st0[R][SD], st1[R][SD], st2[R][SD];
+        u32x4 bw0[R][2], bw1[R][2], bw2[R][2], bw3[R][2];
+        uint32_t wbase[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) wbase[r] = ((uint32_t)rtc[r] * 16u * (uint32_t)a.K + (uint32_t)kr0 * 256u) * 2u;
         int ti = 0, tc = 0;
 #define DZ_ISSUE(buf)                                                                                              \
     do {                                                                                                           \
-        issue_task<BITS, GROUP, R, SD, HAS_BASE, HAS_DELTA>(ci, a, g, rtc, lo, s_seg_blob, (uint32_t)off_idx,        \
-                                                            (uint32_t)off_scale, blob_bytes, w_bytes, buf); \
-        if (++ti < total) advance(ci, kr0, kr1, HAS_BASE);                                                         \
+        delta_issue<BITS, GROUP, R>(ci, g, rtc, lo, s_seg_blob, (uint32_t)off_idx, (uint32_t)off_scale, blob_bytes, \
+                                    buf);                                                                          \
+        if (++ti < nd) advance(ci, kr0, kr1);                                                                      \
     } while (0)
 #define DZ_STEP(cur, nxt)                                                                                          \
     do {                                                                                                           \
         DZ_ISSUE(nxt);                                                                                             \
-        if (tc < total) {                                                                                          \
-            compute_task<BITS, GROUP, R, J, SD, HAS_BASE, HAS_DELTA>(cc, kr0, kr1, cur, xs, g, s_seg_begin, acc, tmp); \
-            advance(cc, kr0, kr1, HAS_BASE);                                                                       \
+        if (tc < nd) {                                                                                             \
+            delta_compute<BITS, GROUP, R, J>(cc, kr0, kr1, cur, xs, g, s_seg_begin, acc, tmp);                     \
+            advance(cc, kr0, kr1);                                                                                 \
         }                                                                                                          \
         ++tc;                                                                                                      \
     } while (0)
-        if (total > 0) {
-            DZ_ISSUE(st0);
-            DZ_ISSUE(st1);
-            while (tc < total) {
+#define DZ_BSTEP(s, cur, nxt)                                                                                      \
+    do {                                                                                                           \
+        base_issue<R>(rw, wbase, lo.w, min((s) + 3, nsteps - 1), nxt);                                             \
+        base_compute<R, J>(cur, xs, g, (s) * 64, acc);                                                             \
+    } while (0)
+        if (kr0 != kt0) __syncthreads();         // previous round's LDS readers are done
+        // ---- x[:, k-slice of this round] -> LDS, rows in sorted order, rows past cnt zero.  The
+        // first weight loads are issued right behind the first batch of x loads (loads return in
+        // order, so x goes first), which overlaps the two latencies.
+        {
+            const int cpr = ntr * 32;            // 16-byte pieces per row
+            const int npieces = 16 * J * cpr;
+            const uint32_t rcp = (65536u + (uint32_t)ntr - 1u) / (uint32_t)ntr;
+            bool primed = false;
+            for (int i0 = tid; i0 < npieces || !primed; i0 += THREADS * 4) {
+                uint4 v[4];
+                int dst[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + u * THREADS;
+                    const int rr = (int)((((uint32_t)i >> 5) * rcp) >> 16);
+                    const int cc2 = i - rr * cpr;
+                    const int tok = (i < npieces) ? s_tok[rr] : -1;
+                    dst[u] = (i < npieces) ? rr * g.LDW + cc2 * 8 : -1;
+                    v[u] = (uint4){0u, 0u, 0u, 0u};
+                    if (tok >= 0) v[u] = *(const uint4 *)(x + (size_t)tok * a.K + (size_t)kr0 * 256 + cc2 * 8);
+                }
+                if (!primed) {
+                    if constexpr (HAS_BASE) {
+                        base_issue<R>(rw, wbase, lo.w, 0, bw0);
+                        base_issue<R>(rw, wbase, lo.w, 1, bw1);
+                        base_issue<R>(rw, wbase, lo.w, 2, bw2);
+                    }
+                    if constexpr (HAS_DELTA) {
+                        if (nd > 0) {
+                            DZ_ISSUE(st0);
+                            DZ_ISSUE(st1);
+                        }
+                    }
+                    primed = true;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (dst[u] >= 0) *(uint4 *)(xs + dst[u]) = v[u];
+            }
+        }
+        __syncthreads();
+        DZ_T(2);
+        if constexpr (HAS_BASE) {
+            for (int s = 0; s < nsteps; s += 4) {
+                DZ_BSTEP(s, bw0, bw3);
+                DZ_BSTEP(s + 1, bw1, bw0);
+                DZ_BSTEP(s + 2, bw2, bw1);
+                DZ_BSTEP(s + 3, bw3, bw2);
+            }
+        }
+        if constexpr (HAS_DELTA) {
+            while (tc < nd) {
                 DZ_STEP(st0, st2);
                 DZ_STEP(st1, st0);
                 DZ_STEP(st2, st1);
@@ -514,8 +538,10 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 4)))
         }
 #undef DZ_ISSUE
 #undef DZ_STEP
+#undef DZ_BSTEP
     }
 
+    DZ_T(3);
     // ---- results: lane 16q + c holds rows 4q..4q+3 of the row tile for request column c
     _Float16 *out = (_Float16 *)a.out;
     if (a.S == 1) {
@@ -532,10 +558,14 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 4)))
     }
 
     // ---- split k: partial tiles meet in fp32.  Partials are written and later read with
-    // agent-scope accesses (coherent across the chip's L2s without flushing them); each wave
-    // waits for its stores to complete before the barrier, then one thread bumps the arrival
-    // counter of the row block.  The last workgroup to arrive adds the slices in fixed order.
+    // agent-scope (sc1) accesses, which are coherent across the chip's L2s without flushing them;
+    // each wave waits for its stores to complete before the barrier, then one thread bumps the
+    // arrival counter of the row block.  The last workgroup to arrive adds the slices in fixed
+    // order (so the result does not depend on arrival order) and rounds once.
+    constexpr int AGENT = 0x10;                  // cache-policy bit sc1
     const int Tp = ((a.T + 63) >> 6) << 6;
+    const uint32_t slice_bytes = (uint32_t)Tp * (uint32_t)a.N * 4u;
+    const __amdgpu_buffer_rsrc_t prs = make_rsrc(a.partial, slice_bytes * (uint32_t)a.S);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         if (!rvalid[r]) continue;
@@ -543,90 +573,98 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 4)))
         for (int j = 0; j < J; ++j) {
             const int pr = 16 * j + g.row;
             if (pr < cnt) {
-                float *p = a.partial + ((size_t)ks * Tp + p0 + pr) * a.N + rtc[r] * 16 + 4 * g.q;
-                if (a.fix_mode == 2) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        __hip_atomic_store(p + i, acc[r][j][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                } else {
-                    *(f4 *)p = acc[r][j];
-                }
+                const uint32_t off = ((uint32_t)(p0 + pr) * (uint32_t)a.N + (uint32_t)rtc[r] * 16u + 4u * g.q) * 4u;
+                const u32x4 v = __builtin_bit_cast(u32x4, acc[r][j]);
+                __builtin_amdgcn_raw_buffer_store_b128(v, prs, off, (uint32_t)ks * slice_bytes, AGENT);
             }
         }
     }
     __builtin_amdgcn_s_waitcnt(0);               // this wave's stores have completed
     __syncthreads();
+    DZ_T(4);
     if (tid == 0) {
         int32_t *ctr = a.counters + chunk * NRB + rb;
-        if (a.fix_mode != 2) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int last = (old == a.S - 1);
-        if (last) {
-            __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
-            if (a.fix_mode != 2) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        }
+        if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
         s_last = last;
     }
     __syncthreads();
+    DZ_T(5);
     if (!s_last) return;
-    const int width = WAVES * R * 16;            // rows of N per row block
-    const int nq = width / 4;
+    constexpr int width = WAVES * R * 16;        // rows of N per row block
+    constexpr int nq = width / 4;
     for (int i = tid; i < cnt * nq; i += THREADS) {
         const int pr = i / nq, c4 = i - pr * nq;
         const int n = rb * width + c4 * 4;
         if (n >= a.N) continue;
+        const uint32_t off = ((uint32_t)(p0 + pr) * (uint32_t)a.N + (uint32_t)n) * 4u;
         f4 sum = (f4){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < a.S; ++s) {
-            const float *p = a.partial + ((size_t)s * Tp + p0 + pr) * a.N + n;
-            if (a.fix_mode == 2) {
+        for (int s0 = 0; s0 < a.S; s0 += 8) {
+            f4 v[8];
 #pragma unroll
-                for (int i2 = 0; i2 < 4; ++i2)
-                    sum[i2] += __hip_atomic_load(p + i2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else {
-                sum += *(const f4 *)p;
+            for (int u = 0; u < 8; ++u) {
+                const int s = min(s0 + u, a.S - 1);
+                v[u] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(prs, off, (uint32_t)s * slice_bytes, AGENT));
             }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < a.S) sum += v[u];
         }
         const int tok = s_tok[pr];
         store_row4(out + (size_t)tok * a.N + n, sum, a.accumulate);
     }
+#ifdef DZ_PROF
+    __builtin_amdgcn_s_waitcnt(0);
+    DZ_T(6);
+#endif
 }
 
-template <int BITS, int GROUP, int R, int J, bool HB, bool HD>
+template <int BITS, int GROUP, int WAVES, int R, int J, bool HB, bool HD>
 hipError_t launch_one(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int round_tiles, int grid,
                       size_t lds, const DzLayout &L, hipStream_t st)
 {
-    auto k = stream_kernel<BITS, GROUP, R, J, HB, HD>;
+    auto k = stream_kernel<BITS, GROUP, WAVES, R, J, HB, HD>;
     static bool attr_set = false;       // per instantiation; the attribute is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(k, dim3(grid), dim3(THREADS), lds, st, a, dp, NRB, round_tiles, L.off_idx, L.off_scale, L.total);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(WAVES * 64), lds, st, a, dp, NRB, round_tiles, L.off_idx, L.off_scale, L.total);
     return hipGetLastError();
 }
 
-template <int BITS, int GROUP, int R, bool HB, bool HD>
+template <int BITS, int GROUP, int WAVES, int R, bool HB, bool HD>
 hipError_t launch_j(int J, const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int rt, int grid, size_t lds,
                     const DzLayout &L, hipStream_t st)
 {
     switch (J) {
-    case 1: return launch_one<BITS, GROUP, R, 1, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
-    case 2: return launch_one<BITS, GROUP, R, 2, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
-    case 3: return launch_one<BITS, GROUP, R, 3, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
-    default: return launch_one<BITS, GROUP, R, 4, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
+    case 1: return launch_one<BITS, GROUP, WAVES, R, 1, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
+    case 2: return launch_one<BITS, GROUP, WAVES, R, 2, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
+    case 3: return launch_one<BITS, GROUP, WAVES, R, 3, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
+    default: return launch_one<BITS, GROUP, WAVES, R, 4, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
     }
 }
 
-template <int R, bool HB, bool HD>
+template <int WAVES, int R, bool HB, bool HD>
 hipError_t launch_fmt(int bits, int group, int J, const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int rt,
                       int grid, size_t lds, const DzLayout &L, hipStream_t st)
 {
-    if (!HD) return launch_j<4, 128, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
-    if (bits == 4 && group == 128) return launch_j<4, 128, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
-    if (bits == 4) return launch_j<4, 64, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
-    if (group == 128) return launch_j<2, 128, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
-    return launch_j<2, 64, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
+    if (!HD) return launch_j<4, 128, WAVES, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
+    if (bits == 4 && group == 128) return launch_j<4, 128, WAVES, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
+    if (bits == 4) return launch_j<4, 64, WAVES, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
+    if (group == 128) return launch_j<2, 128, WAVES, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
+    return launch_j<2, 64, WAVES, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
+}
+
+template <int WAVES, int R>
+hipError_t launch_kind(const DzStreamArgs &a, int J, const DzDeltaPtrs &dp, int NRB, int rt, int grid, size_t lds,
+                       const DzLayout &L, hipStream_t st)
+{
+    if (a.has_base && a.has_delta) return launch_fmt<WAVES, R, true, true>(a.bits, a.group, J, a, dp, NRB, rt, grid, lds, L, st);
+    if (a.has_base) return launch_fmt<WAVES, R, true, false>(a.bits, a.group, J, a, dp, NRB, rt, grid, lds, L, st);
+    return launch_fmt<WAVES, R, false, true>(a.bits, a.group, J, a, dp, NRB, rt, grid, lds, L, st);
 }
 
 }  // namespace
@@ -638,13 +676,15 @@ int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
 int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &dp, hipStream_t st)
 {
     DzStreamArgs a = args;
-    constexpr int R = 2;
+    const int WAVES = ctx->wg_waves, R = ctx->wg_rtiles;
     const int RT = a.N / 16, KT = a.K / 256;
     const int nchunks = (a.T + 63) / 64;
     const int J = (a.T >= 64) ? 4 : (a.T + 15) / 16;
     const int NRB = (RT + WAVES * R - 1) / (WAVES * R);
     const long long units0 = (long long)nchunks * NRB;
-    int S = ctx->force_splits > 0 ? ctx->force_splits : (int)((ctx->target_wgs + units0 - 1) / units0);
+    // as many k slices as keep the workgroup count at or just under the target (a multiple of the
+    // CU count): a few idle slots cost little, one workgroup too many doubles some CU's work
+    int S = ctx->force_splits > 0 ? ctx->force_splits : (int)(ctx->target_wgs / units0);
     if (S > KT) S = KT;
     if (S < 1) S = 1;
     const size_t Tp = (size_t)nchunks * 64;
@@ -668,11 +708,8 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &d
     if ((unsigned long long)a.N * a.K * 2ull >= (1ull << 32)) return DZ_ERR_SHAPE;     // 32-bit byte offsets
     DzLayout L = dz_make_layout(a.N, a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
     hipError_t e;
-    if (a.has_base && a.has_delta)
-        e = launch_fmt<R, true, true>(a.bits, a.group, J, a, dp, NRB, round_tiles, (int)grid, lds, L, st);
-    else if (a.has_base)
-        e = launch_fmt<R, true, false>(a.bits, a.group, J, a, dp, NRB, round_tiles, (int)grid, lds, L, st);
-    else
-        e = launch_fmt<R, false, true>(a.bits, a.group, J, a, dp, NRB, round_tiles, (int)grid, lds, L, st);
+    if (WAVES == 8 && R == 1) e = launch_kind<8, 1>(a, J, dp, NRB, round_tiles, (int)grid, lds, L, st);
+    else if (WAVES == 8 && R == 2) e = launch_kind<8, 2>(a, J, dp, NRB, round_tiles, (int)grid, lds, L, st);
+    else e = launch_kind<4, 2>(a, J, dp, NRB, round_tiles, (int)grid, lds, L, st);
     return dz_set_hip_error(ctx, e);
 }
