@@ -50,7 +50,8 @@ struct DzStreamArgs {
     int32_t *counters;
     int T, N, K, D, bits, group;
     int accumulate;
-    int S;                      // k splits
+    int S;                      // workgroups per chunk of 64 request rows
+    int max_slots;              // most workgroups sharing one row block (partial-sum slots)
     int has_base, has_delta;
 };
 

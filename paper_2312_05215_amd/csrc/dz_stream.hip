@@ -341,12 +341,17 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
     lo.i = (uint32_t)g.lane * 8u;
     lo.s = (uint32_t)g.row * (uint32_t)(F::GPT * 4);
 
-    int unit = blockIdx.x;
-    const int ks = unit % a.S; unit /= a.S;
-    const int rb = unit % NRB;
-    const int chunk = unit / NRB;
-    const int kt0 = (int)((long long)ks * g.KT / a.S);
-    const int kt1 = (int)((long long)(ks + 1) * g.KT / a.S);
+    // Work decomposition: the (row block, k tile) grid of this call, flattened row block by row
+    // block, is cut into G equal contiguous ranges, one per workgroup (G = a.S, a multiple of the
+    // CU count whenever the call is large enough), so every CU streams the same number of bytes
+    // whatever the shape.  A range may end inside a row block and continue in the next one: each
+    // piece is a *segment* with its own partial result.
+    const int G = a.S;
+    const int chunk = blockIdx.x / G;
+    const int wg = blockIdx.x - chunk * G;
+    const long long P = (long long)NRB * g.KT;
+    const int p_begin = (int)((long long)wg * P / G);
+    const int p_end = (int)((long long)(wg + 1) * P / G);
     const int p0 = chunk * 64;
     const int cnt = min(64, a.T - p0);
     const int RT = a.N >> 4;
@@ -418,6 +423,22 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
     __syncthreads();
     DZ_T(1);
 
+    const _Float16 *x = (const _Float16 *)a.x;
+    const uint32_t w_bytes = (uint32_t)a.N * (uint32_t)a.K * 2u;
+    const uint32_t blob_bytes = (uint32_t)blob_total;
+    const int nseg = HAS_DELTA ? s_nseg : 0;
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.W ? a.W : a.x, HAS_BASE ? w_bytes : 0u);
+    _Float16 *out = (_Float16 *)a.out;
+    constexpr int AGENT = 0x10;                  // cache-policy bit sc1
+    const int Tp = ((a.T + 63) >> 6) << 6;
+    const uint32_t slice_bytes = (uint32_t)Tp * (uint32_t)a.N * 4u;
+    const __amdgpu_buffer_rsrc_t prs = make_rsrc(a.partial, slice_bytes * (uint32_t)a.max_slots);
+
+  for (int p = p_begin; p < p_end;) {
+    const int rb = p / g.KT;
+    const int kt0 = p - rb * g.KT;
+    const int kt1 = min(g.KT, kt0 + (p_end - p));
+    p += kt1 - kt0;
     int rtc[R];
     bool rvalid[R];
 #pragma unroll
@@ -426,7 +447,6 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
         rvalid[r] = rt < RT;
         rtc[r] = rvalid[r] ? rt : RT - 1;
     }
-
     f4 acc[R][J], tmp[R][J];
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -435,12 +455,7 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
             acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
             tmp[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
         }
-
-    const _Float16 *x = (const _Float16 *)a.x;
-    const uint32_t w_bytes = (uint32_t)a.N * (uint32_t)a.K * 2u;
-    const uint32_t blob_bytes = (uint32_t)blob_total;
-    const int nseg = HAS_DELTA ? s_nseg : 0;
-    const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.W ? a.W : a.x, HAS_BASE ? w_bytes : 0u);
+    bool first_round = true;
     for (int kr0 = kt0; kr0 < kt1; kr0 += round_tiles) {
         const int kr1 = min(kt1, kr0 + round_tiles);
         const int ntr = kr1 - kr0;
@@ -478,7 +493,8 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
         base_issue<R>(rw, wbase, lo.w, min((s) + 3, nsteps - 1), nxt);                                             \
         base_compute<R, J>(cur, xs, g, (s) * 64, acc);                                                             \
     } while (0)
-        if (kr0 != kt0) __syncthreads();         // previous round's LDS readers are done
+        if (!(first_round && p_begin == p - (kt1 - kt0))) __syncthreads();   // previous LDS readers are done
+        first_round = false;
         // ---- x[:, k-slice of this round] -> LDS, rows in sorted order, rows past cnt zero.  The
         // first weight loads are issued right behind the first batch of x loads (loads return in
         // order, so x goes first), which overlaps the two latencies.
@@ -542,9 +558,13 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
     }
 
     DZ_T(3);
-    // ---- results: lane 16q + c holds rows 4q..4q+3 of the row tile for request column c
-    _Float16 *out = (_Float16 *)a.out;
-    if (a.S == 1) {
+    // ---- results of this segment: lane 16q + c holds rows 4q..4q+3 of the row tile for request
+    // column c.  Which workgroups contribute to row block rb follows from the range formula:
+    // the owner of flat position f is ceil((f + 1) * G / P) - 1.
+    const int w_first = (int)((((long long)rb * g.KT + 1) * G + P - 1) / P) - 1;
+    const int w_last = (int)((((long long)(rb + 1) * g.KT) * G + P - 1) / P) - 1;
+    const int ncontrib = w_last - w_first + 1;
+    if (ncontrib == 1) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (!rvalid[r]) continue;
@@ -554,18 +574,16 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
                 if (tok >= 0) store_row4(out + (size_t)tok * a.N + rtc[r] * 16 + 4 * g.q, acc[r][j], a.accumulate);
             }
         }
-        return;
+        continue;
     }
 
-    // ---- split k: partial tiles meet in fp32.  Partials are written and later read with
-    // agent-scope (sc1) accesses, which are coherent across the chip's L2s without flushing them;
-    // each wave waits for its stores to complete before the barrier, then one thread bumps the
-    // arrival counter of the row block.  The last workgroup to arrive adds the slices in fixed
-    // order (so the result does not depend on arrival order) and rounds once.
-    constexpr int AGENT = 0x10;                  // cache-policy bit sc1
-    const int Tp = ((a.T + 63) >> 6) << 6;
-    const uint32_t slice_bytes = (uint32_t)Tp * (uint32_t)a.N * 4u;
-    const __amdgpu_buffer_rsrc_t prs = make_rsrc(a.partial, slice_bytes * (uint32_t)a.S);
+    // ---- several workgroups share the row block: partial tiles meet in fp32.  Partials are
+    // written and later read with agent-scope (sc1) accesses, which are coherent across the chip's
+    // L2s without flushing them; each wave waits for its stores to complete before the barrier,
+    // then one thread bumps the arrival counter of the row block.  The last workgroup to arrive
+    // adds the slots in fixed order (so the result does not depend on arrival order) and rounds
+    // once.
+    const int slot = wg - w_first;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         if (!rvalid[r]) continue;
@@ -575,7 +593,7 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
             if (pr < cnt) {
                 const uint32_t off = ((uint32_t)(p0 + pr) * (uint32_t)a.N + (uint32_t)rtc[r] * 16u + 4u * g.q) * 4u;
                 const u32x4 v = __builtin_bit_cast(u32x4, acc[r][j]);
-                __builtin_amdgcn_raw_buffer_store_b128(v, prs, off, (uint32_t)ks * slice_bytes, AGENT);
+                __builtin_amdgcn_raw_buffer_store_b128(v, prs, off, (uint32_t)slot * slice_bytes, AGENT);
             }
         }
     }
@@ -585,39 +603,41 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
     if (tid == 0) {
         int32_t *ctr = a.counters + chunk * NRB + rb;
         const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int last = (old == a.S - 1);
+        const int last = (old == ncontrib - 1);
         if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
         s_last = last;
     }
     __syncthreads();
     DZ_T(5);
-    if (!s_last) return;
-    constexpr int width = WAVES * R * 16;        // rows of N per row block
-    constexpr int nq = width / 4;
-    for (int i = tid; i < cnt * nq; i += THREADS) {
-        const int pr = i / nq, c4 = i - pr * nq;
-        const int n = rb * width + c4 * 4;
-        if (n >= a.N) continue;
-        const uint32_t off = ((uint32_t)(p0 + pr) * (uint32_t)a.N + (uint32_t)n) * 4u;
-        f4 sum = (f4){0.f, 0.f, 0.f, 0.f};
-        for (int s0 = 0; s0 < a.S; s0 += 8) {
-            f4 v[8];
+    if (s_last) {
+        constexpr int width = WAVES * R * 16;        // rows of N per row block
+        constexpr int nq = width / 4;
+        for (int i = tid; i < cnt * nq; i += THREADS) {
+            const int pr = i / nq, c4 = i - pr * nq;
+            const int n = rb * width + c4 * 4;
+            if (n >= a.N) continue;
+            const uint32_t off = ((uint32_t)(p0 + pr) * (uint32_t)a.N + (uint32_t)n) * 4u;
+            f4 sum = (f4){0.f, 0.f, 0.f, 0.f};
+            for (int s0 = 0; s0 < ncontrib; s0 += 8) {
+                f4 v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int s = min(s0 + u, a.S - 1);
-                v[u] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(prs, off, (uint32_t)s * slice_bytes, AGENT));
+                for (int u = 0; u < 8; ++u) {
+                    const int sl = min(s0 + u, ncontrib - 1);
+                    v[u] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(prs, off, (uint32_t)sl * slice_bytes, AGENT));
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < ncontrib) sum += v[u];
             }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (s0 + u < a.S) sum += v[u];
+            const int tok = s_tok[pr];
+            store_row4(out + (size_t)tok * a.N + n, sum, a.accumulate);
         }
-        const int tok = s_tok[pr];
-        store_row4(out + (size_t)tok * a.N + n, sum, a.accumulate);
     }
 #ifdef DZ_PROF
     __builtin_amdgcn_s_waitcnt(0);
     DZ_T(6);
 #endif
+  }   // segments
 }
 
 template <int BITS, int GROUP, int WAVES, int R, int J, bool HB, bool HD>
@@ -682,28 +702,36 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &d
     const int J = (a.T >= 64) ? 4 : (a.T + 15) / 16;
     const int NRB = (RT + WAVES * R - 1) / (WAVES * R);
     const long long units0 = (long long)nchunks * NRB;
-    // as many k slices as keep the workgroup count at or just under the target (a multiple of the
-    // CU count): a few idle slots cost little, one workgroup too many doubles some CU's work
-    int S = ctx->force_splits > 0 ? ctx->force_splits : (int)(ctx->target_wgs / units0);
-    if (S > KT) S = KT;
-    if (S < 1) S = 1;
+    // number of workgroups per chunk: the target (a multiple of the CU count) unless the call has
+    // fewer (row block, k tile) positions than that
+    const long long P = (long long)NRB * KT;
+    long long G = ctx->force_splits > 0 ? (long long)ctx->force_splits * NRB : ctx->target_wgs;
+    if (G > P) G = P;
+    if (G < 1) G = 1;
+    // most workgroups that can share one row block = partial slots needed
+    int max_slots = 1;
+    for (int rb = 0; rb < NRB; ++rb) {
+        const long long wf = (((long long)rb * KT + 1) * G + P - 1) / P - 1;
+        const long long wl = (((long long)(rb + 1) * KT) * G + P - 1) / P - 1;
+        if (wl - wf + 1 > max_slots) max_slots = (int)(wl - wf + 1);
+    }
     const size_t Tp = (size_t)nchunks * 64;
-    // keep the partial-sum workspace modest
-    while (S > 1 && (size_t)S * Tp * a.N * 4 > ((size_t)256 << 20)) --S;
+    if ((size_t)max_slots * Tp * a.N * 4 >= ((size_t)1 << 32)) return DZ_ERR_SHAPE;    // 32-bit byte offsets
     int round_tiles = ctx->round_tiles > 0 ? ctx->round_tiles : (J <= 2 ? 4 : 2);
-    const int max_slice = (KT + S - 1) / S;
+    const int max_slice = (int)((P + G - 1) / G) < KT ? (int)((P + G - 1) / G) : KT;
     if (round_tiles > max_slice) round_tiles = max_slice;
     const size_t lds = (size_t)16 * J * (round_tiles * 256 + LDS_PAD) * sizeof(_Float16);
-    a.S = S;
-    if (S > 1) {
-        int rc = dz_ensure_partial(ctx, (size_t)S * Tp * a.N * 4, st);
+    a.S = (int)G;
+    a.max_slots = max_slots;
+    if (max_slots > 1) {
+        int rc = dz_ensure_partial(ctx, (size_t)max_slots * Tp * a.N * 4, st);
         if (rc) return rc;
         rc = dz_ensure_counters(ctx, (int)units0, st);
         if (rc) return rc;
     }
     a.partial = ctx->partial;
     a.counters = ctx->counters;
-    const long long grid = units0 * S;
+    const long long grid = (long long)nchunks * G;
     if (grid > 0x7fffffffLL) return DZ_ERR_SHAPE;
     if ((unsigned long long)a.N * a.K * 2ull >= (1ull << 32)) return DZ_ERR_SHAPE;     // 32-bit byte offsets
     DzLayout L = dz_make_layout(a.N, a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
