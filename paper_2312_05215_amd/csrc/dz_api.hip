@@ -131,8 +131,8 @@ int dz_create(dz_ctx **out, int device)
     ctx->force_splits = env_int("DZ_SPLITS", 0);
     ctx->target_wgs = env_int("DZ_TARGET_WGS", 512);
     if (ctx->target_wgs < 1) ctx->target_wgs = 1;
-    ctx->wg_waves = env_int("DZ_WAVES", 8);
-    ctx->wg_rtiles = env_int("DZ_RTILES", 1);
+    ctx->wg_waves = env_int("DZ_WAVES", 0);
+    ctx->wg_rtiles = env_int("DZ_RTILES", 0);
     ctx->round_tiles = env_int("DZ_ROUND_TILES", 0);
     DeviceGuard guard(device);
     hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;

@@ -45,6 +45,13 @@ __device__ inline unsigned lanes_below(unsigned long long m)
     return __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load (vmcnt(0)), which would drain the weight prefetch at each barrier.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
 
 template <int ABID>
@@ -102,11 +109,12 @@ struct Geo {
     int LDW;                // LDS row stride in halfs
 };
 
-// B operand of one step for column block j: lane 16b + c reads request row 16j + c,
-// k = 8b..8b+7 (slots 0-7) and 32+8b..32+8b+7 (slots 8-15) of the step.
-__device__ __forceinline__ h16 load_b(const _Float16 *xs, const Geo &g, int j, int kofs)
+// B operand of one step for one column block: lane 16b + c reads the LDS row of its request
+// column (boff = that row's offset in halfs), k = 8b..8b+7 (slots 0-7) and 32+8b..32+8b+7
+// (slots 8-15) of the step.
+__device__ __forceinline__ h16 load_b(const _Float16 *xs, int boff, const Geo &g, int kofs)
 {
-    const _Float16 *p = xs + (16 * j + g.row) * g.LDW + kofs + 8 * g.q;
+    const _Float16 *p = xs + boff + kofs + 8 * g.q;
     h8 lo = *(const h8 *)p;
     h8 hi = *(const h8 *)(p + 32);
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
@@ -164,12 +172,12 @@ __device__ __forceinline__ void base_issue(__amdgpu_buffer_rsrc_t rw, const uint
 }
 
 template <int R, int J>
-__device__ __forceinline__ void base_compute(const u32x4 (&buf)[R][2], const _Float16 *xs, const Geo &g, int kofs,
-                                             f4 (&acc)[R][J])
+__device__ __forceinline__ void base_compute(const u32x4 (&buf)[R][2], const _Float16 *xs, const Geo &g,
+                                             const int (&brow)[J], int kofs, f4 (&acc)[R][J])
 {
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const h16 b = load_b(xs, g, j, kofs);
+        const h16 b = load_b(xs, brow[j], g, kofs);
         const h8 b0 = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, 6, 7);
         const h8 b1 = __builtin_shufflevector(b, b, 8, 9, 10, 11, 12, 13, 14, 15);
 #pragma unroll
@@ -187,16 +195,19 @@ struct Cursor {
 };
 
 template <int BITS, int GROUP, int R>
-__device__ __forceinline__ void delta_issue(const Cursor &c, const Geo &g, const int (&rtc)[R], const LaneOffs &lo,
-                                            const unsigned long long *s_seg_blob, uint32_t off_idx,
-                                            uint32_t off_scale, uint32_t blob_bytes,
+__device__ __forceinline__ void delta_issue(const Cursor &c, bool valid, const Geo &g, const int (&rtc)[R], const LaneOffs &lo,
+                                            const unsigned long long *s_dptr, const int *s_seg_delta,
+                                            uint32_t off_idx, uint32_t off_scale, uint32_t blob_bytes,
                                             uint32_t (&st)[R][Fmt<BITS, GROUP>::SD])
 {
     typedef Fmt<BITS, GROUP> F;
-    const unsigned long long bp = s_seg_blob[c.seg];
+    // With no delta task in this round the loads are still issued (so the load count never
+    // depends on a branch) but against an empty resource: the hardware returns zeros and touches
+    // no memory.
+    const unsigned long long bp = s_dptr[valid ? s_seg_delta[c.seg] : 0];
     const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)bp);
     const uint32_t h = __builtin_amdgcn_readfirstlane((uint32_t)(bp >> 32));
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc((const void *)(((unsigned long long)h << 32) | l), blob_bytes);
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc((const void *)(((unsigned long long)h << 32) | l), valid ? blob_bytes : 0u);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const uint32_t tile = (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)c.kt;
@@ -220,7 +231,7 @@ __device__ __forceinline__ void delta_issue(const Cursor &c, const Geo &g, const
 // The four steps of one packed tile against column blocks j0 .. j0 + C - 1.
 template <int BITS, int GROUP, int R, int J, int C>
 __device__ __forceinline__ void delta_steps(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], const _Float16 *xs,
-                                            const Geo &g, int kofs, int j0, f4 (&tmp)[R][J])
+                                            const Geo &g, int kofs, const int (&boff)[C], f4 (&tmp)[R][J])
 {
     typedef Fmt<BITS, GROUP> F;
 #pragma unroll
@@ -239,7 +250,7 @@ __device__ __forceinline__ void delta_steps(const uint32_t (&st)[R][Fmt<BITS, GR
         }
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            const h16 b = load_b(xs, g, j0 + c, kofs + s * 64);
+            const h16 b = load_b(xs, boff[c], g, kofs + s * 64);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 if (s & 1) tmp[r][c] = smfmac<1>(av[r], b, tmp[r][c], (int)idxw[r]);
@@ -253,7 +264,8 @@ __device__ __forceinline__ void delta_steps(const uint32_t (&st)[R][Fmt<BITS, GR
 template <int BITS, int GROUP, int R, int J>
 __device__ __forceinline__ void delta_compute(const Cursor &c, int kr0, int kr1,
                                               const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], const _Float16 *xs,
-                                              const Geo &g, const int *s_seg_begin, f4 (&acc)[R][J], f4 (&tmp)[R][J])
+                                              const Geo &g, const int *s_seg_begin, const int *s_boff,
+                                              f4 (&acc)[R][J], f4 (&tmp)[R][J])
 {
     const int sb = __builtin_amdgcn_readfirstlane(s_seg_begin[c.seg]);
     const int se = __builtin_amdgcn_readfirstlane(s_seg_begin[c.seg + 1]);
@@ -266,10 +278,32 @@ __device__ __forceinline__ void delta_compute(const Cursor &c, int kr0, int kr1,
             for (int j = 0; j < J; ++j) tmp[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
     }
     const int kofs = (c.kt - kr0) * 256;
-    if (C == 1) delta_steps<BITS, GROUP, R, J, 1>(st, xs, g, kofs, j0, tmp);
-    else if (J >= 2 && C == 2) delta_steps<BITS, GROUP, R, J, (J >= 2 ? 2 : 1)>(st, xs, g, kofs, j0, tmp);
-    else if (J >= 3 && C == 3) delta_steps<BITS, GROUP, R, J, (J >= 3 ? 3 : 1)>(st, xs, g, kofs, j0, tmp);
-    else if (J >= 4 && C == 4) delta_steps<BITS, GROUP, R, J, (J >= 4 ? 4 : 1)>(st, xs, g, kofs, j0, tmp);
+    // LDS rows of this lane's request column in each overlapped block
+    int boff[J];
+#pragma unroll
+    for (int cc = 0; cc < J; ++cc) boff[cc] = s_boff[min(16 * (j0 + cc), 48) + g.row];
+    if (C == 1) {
+        const int b1[1] = {boff[0]};
+        delta_steps<BITS, GROUP, R, J, 1>(st, xs, g, kofs, b1, tmp);
+    }
+    if constexpr (J >= 2) {
+        if (C == 2) {
+            const int b2[2] = {boff[0], boff[1]};
+            delta_steps<BITS, GROUP, R, J, 2>(st, xs, g, kofs, b2, tmp);
+        }
+    }
+    if constexpr (J >= 3) {
+        if (C == 3) {
+            const int b3[3] = {boff[0], boff[1], boff[2]};
+            delta_steps<BITS, GROUP, R, J, 3>(st, xs, g, kofs, b3, tmp);
+        }
+    }
+    if constexpr (J >= 4) {
+        if (C == 4) {
+            const int b4[4] = {boff[0], boff[1], boff[2], boff[3]};
+            delta_steps<BITS, GROUP, R, J, 4>(st, xs, g, kofs, b4, tmp);
+        }
+    }
     if (c.kt == kr1 - 1) {
         // merge: only the columns (sorted positions) that belong to this segment
 #pragma unroll
@@ -307,18 +341,22 @@ __device__ __forceinline__ void store_row4(_Float16 *p, f4 v, int accumulate)
 
 
 template <int BITS, int GROUP, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
-__global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((WAVES * R <= 8 && J <= 2) ? 4 : 2)))
+void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
                                                             size_t off_idx, size_t off_scale, size_t blob_total)
 {
     typedef Fmt<BITS, GROUP> F;
     constexpr int SD = F::SD;
     constexpr int THREADS = WAVES * 64;
-    extern __shared__ __attribute__((aligned(16))) _Float16 xs[];     // [16J][LDW]
+    constexpr int ZROW = 16 * J;            // an all-zero LDS row for column slots without a request
+    extern __shared__ __attribute__((aligned(16))) _Float16 xs[];     // [16J + 1][LDW]
     __shared__ int s_tok[64];               // request row of each sorted position (-1: none)
     __shared__ int s_key[64];               // delta of each sorted position
     __shared__ int s_raw[64];
     __shared__ int s_rank[64];
-    __shared__ unsigned long long s_seg_blob[64];
+    __shared__ int s_boff[64];              // LDS offset (halfs) of the x row of each sorted position
+    __shared__ unsigned long long s_dptr[DZ_MAX_DELTAS];   // packed-delta pointers (copied from the arguments)
+    __shared__ int s_seg_delta[64];
     __shared__ int s_seg_begin[65];
     __shared__ int s_nseg;
     __shared__ int s_last;
@@ -356,83 +394,45 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
     const int cnt = min(64, a.T - p0);
     const int RT = a.N >> 4;
 
-    // ---- sorted order of this chunk's request rows (paper Section 5.2: requests of one delta are
-    // grouped).  Up to 64 rows are ranked here by every workgroup from the raw index vector (rank =
-    // rows with a smaller delta + earlier rows with the same delta), which saves a launch and a
-    // dependent load; larger batches read the order a segment pass left in the workspace.
-    if (HAS_DELTA && a.ids) {
+    // Request order (paper Section 5.2: requests of one delta are grouped).  Batches of up to 64
+    // rows are ranked by every workgroup itself from the raw index vector (rank = rows with a
+    // smaller delta + earlier rows of the same delta) -- no extra launch and no dependent load;
+    // x then sits in LDS in request order and a lane finds the row of its column through s_boff.
+    // Larger batches read the sorted order a segment pass left in the workspace and stage x rows
+    // already sorted.
+    const bool sort_here = HAS_DELTA && a.ids != nullptr;
+    if (HAS_DELTA && tid < max(a.D, 1)) s_dptr[tid] = tid < a.D ? (unsigned long long)dp.p[tid] : (unsigned long long)a.x;   // before any long-latency load
+    int my_id = -1;
+    if (sort_here && tid < cnt) my_id = a.ids[tid];                 // earliest possible load
+    if (!sort_here) {
         if (tid < 64) {
-            int key = INT_MAX;
+            int tok = -1, key = INT_MAX;
             if (tid < cnt) {
-                const int id = a.ids[tid];
-                const bool valid = id >= 0 && id < a.D;
-                key = valid ? id : a.D;
-                if (!valid && id != -1 && blockIdx.x == 0) atomicOr(a.err_flag, 1);
+                tok = a.perm ? a.perm[p0 + tid] : p0 + tid;
+                if (HAS_DELTA && a.key) key = a.key[p0 + tid];
             }
-            s_raw[tid] = key;
-            s_rank[tid] = 0;
+            s_tok[tid] = tok;
+            s_key[tid] = key;
+            s_boff[tid] = tid * g.LDW;
         }
-        __syncthreads();
-        {
-            constexpr int PER = 64 / WAVES;     // each wave compares against its share of the rows
-            const int t = tid & 63, part = tid >> 6;
-            const int kme = s_raw[t];
-            int c = 0;
-#pragma unroll
-            for (int jj = 0; jj < PER; ++jj) {
-                const int j = part * PER + jj;
-                const int kj = s_raw[j];
-                c += (kj < kme || (kj == kme && j < t)) ? 1 : 0;
-            }
-            atomicAdd(&s_rank[t], c);
-        }
-        __syncthreads();
-        if (tid < 64) {
-            const int r = s_rank[tid];
-            s_tok[r] = tid < cnt ? tid : -1;
-            s_key[r] = s_raw[tid];
-        }
-    } else if (tid < 64) {
-        int tok = -1, key = INT_MAX;
-        if (tid < cnt) {
-            tok = a.perm ? a.perm[p0 + tid] : p0 + tid;
-            if (HAS_DELTA && a.key) key = a.key[p0 + tid];
-        }
-        s_tok[tid] = tok;
-        s_key[tid] = key;
+        lds_barrier();
     }
-    __syncthreads();
-    if (HAS_DELTA && tid < 64) {
-        const int key = s_key[tid];
-        const int prev = tid ? s_key[tid - 1] : -1;
-        const bool valid = key >= 0 && key < a.D;
-        const bool start = valid && (tid == 0 || prev != key);
-        const unsigned long long sm = __ballot(start);
-        const unsigned long long vm = __ballot(valid);
-        if (start) {
-            const int i = (int)lanes_below(sm);
-            s_seg_blob[i] = (unsigned long long)dp.p[key];
-            s_seg_begin[i] = tid;
-        }
-        if (tid == 0) {
-            const int ns = __builtin_popcountll(sm);
-            s_nseg = ns;
-            s_seg_begin[ns] = __builtin_popcountll(vm);     // rows that name a delta are a prefix
-        }
-    }
-    __syncthreads();
-    DZ_T(1);
 
     const _Float16 *x = (const _Float16 *)a.x;
     const uint32_t w_bytes = (uint32_t)a.N * (uint32_t)a.K * 2u;
     const uint32_t blob_bytes = (uint32_t)blob_total;
-    const int nseg = HAS_DELTA ? s_nseg : 0;
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.W ? a.W : a.x, HAS_BASE ? w_bytes : 0u);
     _Float16 *out = (_Float16 *)a.out;
     constexpr int AGENT = 0x10;                  // cache-policy bit sc1
     const int Tp = ((a.T + 63) >> 6) << 6;
     const uint32_t slice_bytes = (uint32_t)Tp * (uint32_t)a.N * 4u;
     const __amdgpu_buffer_rsrc_t prs = make_rsrc(a.partial, slice_bytes * (uint32_t)a.max_slots);
+    bool tables_ready = !sort_here;
+    bool first_round = true;
+    int nseg = 0;
+    int brow[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) brow[j] = 0;
 
   for (int p = p_begin; p < p_end;) {
     const int rb = p / g.KT;
@@ -455,12 +455,11 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
             acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
             tmp[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
         }
-    bool first_round = true;
     for (int kr0 = kt0; kr0 < kt1; kr0 += round_tiles) {
         const int kr1 = min(kt1, kr0 + round_tiles);
         const int ntr = kr1 - kr0;
-        const int nd = nseg * ntr;               // delta tasks of this round
         const int nsteps = 4 * ntr;              // base steps of this round
+        int nd = nseg * ntr;                     // delta tasks of this round (set after the sort in round one)
         Cursor ci, cc;
         ci.kt = kr0; ci.seg = 0;
         cc = ci;
@@ -475,7 +474,7 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
         int ti = 0, tc = 0;
 #define DZ_ISSUE(buf)                                                                                              \
     do {                                                                                                           \
-        delta_issue<BITS, GROUP, R>(ci, g, rtc, lo, s_seg_blob, (uint32_t)off_idx, (uint32_t)off_scale, blob_bytes, \
+        delta_issue<BITS, GROUP, R>(ci, nd > 0, g, rtc, lo, s_dptr, s_seg_delta, (uint32_t)off_idx, (uint32_t)off_scale, blob_bytes, \
                                     buf);                                                                          \
         if (++ti < nd) advance(ci, kr0, kr1);                                                                      \
     } while (0)
@@ -483,7 +482,7 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
     do {                                                                                                           \
         DZ_ISSUE(nxt);                                                                                             \
         if (tc < nd) {                                                                                             \
-            delta_compute<BITS, GROUP, R, J>(cc, kr0, kr1, cur, xs, g, s_seg_begin, acc, tmp);                     \
+            delta_compute<BITS, GROUP, R, J>(cc, kr0, kr1, cur, xs, g, s_seg_begin, s_boff, acc, tmp);             \
             advance(cc, kr0, kr1);                                                                                 \
         }                                                                                                          \
         ++tc;                                                                                                      \
@@ -491,51 +490,119 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
 #define DZ_BSTEP(s, cur, nxt)                                                                                      \
     do {                                                                                                           \
         base_issue<R>(rw, wbase, lo.w, min((s) + 3, nsteps - 1), nxt);                                             \
-        base_compute<R, J>(cur, xs, g, (s) * 64, acc);                                                             \
+        base_compute<R, J>(cur, xs, g, brow, (s) * 64, acc);                                                       \
     } while (0)
-        if (!(first_round && p_begin == p - (kt1 - kt0))) __syncthreads();   // previous LDS readers are done
-        first_round = false;
-        // ---- x[:, k-slice of this round] -> LDS, rows in sorted order, rows past cnt zero.  The
-        // first weight loads are issued right behind the first batch of x loads (loads return in
-        // order, so x goes first), which overlaps the two latencies.
-        {
-            const int cpr = ntr * 32;            // 16-byte pieces per row
-            const int npieces = 16 * J * cpr;
-            const uint32_t rcp = (65536u + (uint32_t)ntr - 1u) / (uint32_t)ntr;
-            bool primed = false;
-            for (int i0 = tid; i0 < npieces || !primed; i0 += THREADS * 4) {
-                uint4 v[4];
-                int dst[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = i0 + u * THREADS;
-                    const int rr = (int)((((uint32_t)i >> 5) * rcp) >> 16);
-                    const int cc2 = i - rr * cpr;
-                    const int tok = (i < npieces) ? s_tok[rr] : -1;
-                    dst[u] = (i < npieces) ? rr * g.LDW + cc2 * 8 : -1;
-                    v[u] = (uint4){0u, 0u, 0u, 0u};
-                    if (tok >= 0) v[u] = *(const uint4 *)(x + (size_t)tok * a.K + (size_t)kr0 * 256 + cc2 * 8);
-                }
-                if (!primed) {
-                    if constexpr (HAS_BASE) {
-                        base_issue<R>(rw, wbase, lo.w, 0, bw0);
-                        base_issue<R>(rw, wbase, lo.w, 1, bw1);
-                        base_issue<R>(rw, wbase, lo.w, 2, bw2);
-                    }
-                    if constexpr (HAS_DELTA) {
-                        if (nd > 0) {
-                            DZ_ISSUE(st0);
-                            DZ_ISSUE(st1);
-                        }
-                    }
-                    primed = true;
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (dst[u] >= 0) *(uint4 *)(xs + dst[u]) = v[u];
-            }
+        if (!first_round) lds_barrier();       // previous LDS readers are done
+        // ---- x[:, k-slice of this round] -> LDS (rows past cnt zero).  Order of issue: x first
+        // (loads return in order and x is needed first), then the first weight loads, which then
+        // fly while the batch is being sorted and x is written to LDS.
+        const int cpr = ntr * 32;                // 16-byte pieces per row
+        const int npieces = 16 * J * cpr;
+        const uint32_t rcp = (65536u + (uint32_t)ntr - 1u) / (uint32_t)ntr;
+        constexpr int XB = 2;                    // x pieces per thread and batch
+        uint4 xv[XB];
+        int xdst[XB];
+#define DZ_XLOAD(i0)                                                                                               \
+    do {                                                                                                           \
+        _Pragma("unroll") for (int u = 0; u < XB; ++u) {                                                          \
+            const int i = (i0) + u * THREADS;                                                                      \
+            const int rr = (int)((((uint32_t)i >> 5) * rcp) >> 16);                                                \
+            const int cc2 = i - rr * cpr;                                                                          \
+            int tok = -1;                                                                                          \
+            if (i < npieces) tok = sort_here ? (rr < cnt ? rr : -1) : s_tok[rr];                                   \
+            xdst[u] = (i < npieces) ? rr * g.LDW + cc2 * 8 : -1;                                                   \
+            xv[u] = (uint4){0u, 0u, 0u, 0u};                                                                       \
+            if (tok >= 0) xv[u] = *(const uint4 *)(x + (size_t)tok * a.K + (size_t)kr0 * 256 + cc2 * 8);          \
+        }                                                                                                          \
+    } while (0)
+#define DZ_XSTORE()                                                                                                \
+    do {                                                                                                           \
+        _Pragma("unroll") for (int u = 0; u < XB; ++u)                                                            \
+            if (xdst[u] >= 0) *(uint4 *)(xs + xdst[u]) = xv[u];                                                    \
+    } while (0)
+        // all batches but the last go to LDS right away (nothing else is in flight yet); the last
+        // batch stays in registers while the weight prefetch is issued behind it
+        int xb0 = 0;
+        for (; xb0 + THREADS * XB < npieces; xb0 += THREADS * XB) {
+            DZ_XLOAD(xb0 + tid);
+            DZ_XSTORE();
         }
-        __syncthreads();
+        DZ_XLOAD(xb0 + tid);
+        if constexpr (HAS_BASE) {
+            base_issue<R>(rw, wbase, lo.w, 0, bw0);
+            base_issue<R>(rw, wbase, lo.w, min(1, nsteps - 1), bw1);
+            base_issue<R>(rw, wbase, lo.w, min(2, nsteps - 1), bw2);
+        }
+        if (!tables_ready) {
+            // ---- rank the batch (all threads; four short barriers)
+            if (tid < 64) {
+                int key = INT_MAX;
+                if (tid < cnt) {
+                    const bool valid = my_id >= 0 && my_id < a.D;
+                    key = valid ? my_id : a.D;
+                    if (!valid && my_id != -1 && blockIdx.x == 0) atomicOr(a.err_flag, 1);
+                }
+                s_raw[tid] = key;
+                s_rank[tid] = 0;
+            }
+            lds_barrier();
+            {
+                constexpr int PER = 64 / WAVES;     // each wave compares against its share of the rows
+                const int t = tid & 63, part = tid >> 6;
+                const int kme = s_raw[t];
+                int c = 0;
+#pragma unroll
+                for (int jj = 0; jj < PER; ++jj) {
+                    const int j = part * PER + jj;
+                    const int kj = s_raw[j];
+                    c += (kj < kme || (kj == kme && j < t)) ? 1 : 0;
+                }
+                atomicAdd(&s_rank[t], c);
+            }
+            lds_barrier();
+            if (tid < 64) {
+                const int r = s_rank[tid];
+                s_tok[r] = tid < cnt ? tid : -1;
+                s_key[r] = s_raw[tid];
+                s_boff[r] = (tid < cnt ? tid : ZROW) * g.LDW;
+            }
+            lds_barrier();
+        }
+        if (first_round) {
+            if (HAS_DELTA && tid < 64) {
+                const int key = s_key[tid];
+                const int prev = tid ? s_key[tid - 1] : -1;
+                const bool valid = key >= 0 && key < a.D;
+                const bool start = valid && (tid == 0 || prev != key);
+                const unsigned long long sm = __ballot(start);
+                const unsigned long long vm = __ballot(valid);
+                if (start) {
+                    const int i = (int)lanes_below(sm);
+                    s_seg_delta[i] = key;
+                    s_seg_begin[i] = tid;
+                }
+                if (tid == 0) {
+                    const int ns = __builtin_popcountll(sm);
+                    s_nseg = ns;
+                    s_seg_begin[ns] = __builtin_popcountll(vm);     // rows that name a delta are a prefix
+                }
+            }
+            if (tid < g.LDW / 8) *(uint4 *)(xs + ZROW * g.LDW + tid * 8) = (uint4){0u, 0u, 0u, 0u};
+            lds_barrier();
+            tables_ready = true;
+            nseg = HAS_DELTA ? s_nseg : 0;
+            nd = nseg * ntr;
+#pragma unroll
+            for (int j = 0; j < J; ++j) brow[j] = s_boff[16 * j + g.row];
+            DZ_T(1);
+        }
+        if constexpr (HAS_DELTA) {
+            DZ_ISSUE(st0);
+            DZ_ISSUE(st1);
+        }
+        DZ_XSTORE();
+        lds_barrier();
+        first_round = false;
         DZ_T(2);
         if constexpr (HAS_BASE) {
             for (int s = 0; s < nsteps; s += 4) {
@@ -555,6 +622,8 @@ __global__ __launch_bounds__(WAVES * 64) void stream_kernel(DzStreamArgs a, DzDe
 #undef DZ_ISSUE
 #undef DZ_STEP
 #undef DZ_BSTEP
+#undef DZ_XLOAD
+#undef DZ_XSTORE
     }
 
     DZ_T(3);
@@ -647,7 +716,7 @@ hipError_t launch_one(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int
     auto k = stream_kernel<BITS, GROUP, WAVES, R, J, HB, HD>;
     static bool attr_set = false;       // per instantiation; the attribute is idempotent
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048);
+        hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -696,10 +765,14 @@ int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
 int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &dp, hipStream_t st)
 {
     DzStreamArgs a = args;
-    const int WAVES = ctx->wg_waves, R = ctx->wg_rtiles;
     const int RT = a.N / 16, KT = a.K / 256;
     const int nchunks = (a.T + 63) / 64;
     const int J = (a.T >= 64) ? 4 : (a.T + 15) / 16;
+    // workgroup shape: few request columns -> 8 waves x 1 row tile (most waves in flight); three or
+    // four column blocks -> 4 waves x 2 row tiles (each B fragment read from LDS feeds two MFMAs,
+    // which the 2-bit format needs to stay under the LDS bandwidth)
+    int WAVES = ctx->wg_waves, R = ctx->wg_rtiles;
+    if (WAVES <= 0 || R <= 0) { WAVES = (J <= 2) ? 8 : 4; R = (J <= 2) ? 1 : 2; }
     const int NRB = (RT + WAVES * R - 1) / (WAVES * R);
     const long long units0 = (long long)nchunks * NRB;
     // number of workgroups per chunk: the target (a multiple of the CU count) unless the call has
@@ -717,10 +790,12 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &d
     }
     const size_t Tp = (size_t)nchunks * 64;
     if ((size_t)max_slots * Tp * a.N * 4 >= ((size_t)1 << 32)) return DZ_ERR_SHAPE;    // 32-bit byte offsets
-    int round_tiles = ctx->round_tiles > 0 ? ctx->round_tiles : (J <= 2 ? 4 : 2);
+    // one batch of x loads per thread must cover a round (see XB in the kernel)
+    const int round_cap = (J <= 2 ? 4 : 2);
+    int round_tiles = (ctx->round_tiles > 0 && ctx->round_tiles < round_cap) ? ctx->round_tiles : round_cap;
     const int max_slice = (int)((P + G - 1) / G) < KT ? (int)((P + G - 1) / G) : KT;
     if (round_tiles > max_slice) round_tiles = max_slice;
-    const size_t lds = (size_t)16 * J * (round_tiles * 256 + LDS_PAD) * sizeof(_Float16);
+    const size_t lds = (size_t)(16 * J + 1) * (round_tiles * 256 + LDS_PAD) * sizeof(_Float16);
     a.S = (int)G;
     a.max_slots = max_slots;
     if (max_slots > 1) {
