@@ -134,6 +134,7 @@ int dz_create(dz_ctx **out, int device)
     ctx->wg_waves = env_int("DZ_WAVES", 0);
     ctx->wg_rtiles = env_int("DZ_RTILES", 0);
     ctx->round_tiles = env_int("DZ_ROUND_TILES", 0);
+    ctx->no_prefill = env_int("DZ_NO_PREFILL", 0);
     DeviceGuard guard(device);
     hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->err_flag, 4);
@@ -267,6 +268,8 @@ static int run_linear(dz_ctx *ctx, const void *x, const void *W, const void *con
         a.perm = ctx->seg_perm;
         a.key = ctx->seg_key;
     }
+    // small batches: HBM-bound streaming kernel; large batches: MFMA-bound tiled kernel
+    if (T > 64 && !ctx->no_prefill) return dz_launch_prefill(ctx, a, dp, st);
     return dz_launch_stream(ctx, a, dp, st);
 }
 

@@ -24,6 +24,7 @@ struct dz_ctx {
     int force_splits;       // DZ_SPLITS
     int target_wgs;         // DZ_TARGET_WGS
     int round_tiles;        // DZ_ROUND_TILES
+    int no_prefill;         // DZ_NO_PREFILL: serve large batches with the streaming kernel (chunks of 64 rows)
     int wg_waves, wg_rtiles; // DZ_WAVES, DZ_RTILES: workgroup shape of the streaming kernel
 #ifdef DZ_PROF
     long long *prof;
@@ -63,3 +64,4 @@ int dz_launch_unpack(dz_ctx *, const void *, int, int, int, int, uint8_t *, uint
 int dz_launch_segment(dz_ctx *, const int32_t *ids, int T, int D, int32_t *counts, int32_t *offsets,
                       int32_t *perm, int32_t *key, hipStream_t);
 int dz_launch_stream(dz_ctx *, const DzStreamArgs &, const DzDeltaPtrs &, hipStream_t);
+int dz_launch_prefill(dz_ctx *, const DzStreamArgs &, const DzDeltaPtrs &, hipStream_t);
