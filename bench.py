@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--workload", default="7b_decode", choices=["7b_decode", "7b_decode_many", "tiny"])
     ap.add_argument("--layers", type=int, default=0, help="distinct resident layers (0 = all of the model)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 --pmc counters)")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
 
@@ -91,6 +93,13 @@ def main():
             for N, K, W, packed, x, out in row:
                 dz.dz_linear(ctx.h, x, W, packed, d_ids, out, cfg.T, N, K, cfg.bits, cfg.group)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # 1 GiB read + 1 GiB written by one elementwise kernel
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     assert dz.dz_check(ctx.h) == dz.DZ_OK
@@ -114,8 +123,15 @@ def main():
     bytes_per_step = n_layers * sum(S.algorithmic_bytes(N, K, cfg.T, cfg.bits, cfg.group, n_active) for _, N, K in projs)
     avg_launch_us = ms_per_step * 1e3 / launches_per_step
     achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+    traffic = None      # measured HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, see profiles/)
+    try:
+        for ln in open(os.path.join(ROOT, "profiles", "stream_kernel_7b_decode_pmc.txt")):
+            if ln.startswith("traffic_bytes_per_launch:") and cfg.name == "7b_decode":
+                traffic = int(ln.split(":")[1])
+    except OSError:
+        pass
     roofline = {"bound": "hbm", "kernel": "stream_kernel (fused base GEMM + SBMM)", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "bytes_per_launch_avg": bytes_per_step // launches_per_step,
                 "avg_launch_us": round(avg_launch_us, 2), "launches_per_step": launches_per_step}
 

@@ -33,7 +33,7 @@
 namespace {
 
 template <int BITS, int GROUP, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((WAVES * R <= 8 && J <= 2) ? 4 : 2)))
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((R == 1 && J <= 2) ? 4 : 2)))
 void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
                                                             size_t off_idx, size_t off_scale, size_t blob_total)
 {
