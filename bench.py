@@ -141,16 +141,20 @@ def main():
         import oracle
         idn = ids.numpy()
         t1 = time.time()
-        for name, N, K, W, tabs, x in host_layer0:
-            dense = [oracle.c.dequant(t.codes.numpy(), t.idx.numpy(), t.scale.numpy(), t.zero.numpy(), cfg.bits, cfg.group)
-                     for t in tabs]
-            oracle.c.linear(x.numpy(), W.numpy(), dense, idn)
-            del dense
-        cpu_s = time.time() - t1
+        passes = 0
+        while passes == 0 or time.time() - t1 < 10.0:      # about 10 s of CPU work, whole passes over layer 0
+            for name, N, K, W, tabs, x in host_layer0:
+                dense = [oracle.c.dequant(t.codes.numpy(), t.idx.numpy(), t.scale.numpy(), t.zero.numpy(), cfg.bits, cfg.group)
+                         for t in tabs]
+                oracle.c.linear(x.numpy(), W.numpy(), dense, idn)
+                del dense
+            passes += 1
+        cpu_s = (time.time() - t1) / passes
         cpu = {"value": round(cfg.T / (cpu_s * cfg.layers), 4), "unit": "tokens/s", "cores": oracle.c.num_threads(),
                "kind": "oracle",
-               "sample": f"layer 0 of {cfg.layers} (all {len(projs)} projections, dense dequantisation of {cfg.D} deltas "
-                         f"+ per-request dot products) took {cpu_s:.1f} s; value extrapolates x{cfg.layers} layers"}
+               "sample": f"layer 0 of {cfg.layers} (all {len(projs)} projections: dense dequantisation of {cfg.D} deltas "
+                         f"+ per-request dot products), {passes} passes, {cpu_s:.2f} s per pass; value extrapolates "
+                         f"x{cfg.layers} layers"}
 
     line = {
         "metric": "SBMM+base decode tokens/s and achieved HBM GB/s (% of peak) per layer",
