@@ -2,84 +2,130 @@
 //
 //   out[t] = f16( x[t] . W^T + x[t] . Delta_{Idx[t]}^T )      (paper Section 5.1 Eq. (2); Section 5.2)
 //
-// With hundreds of request rows per delta the path is a dense contraction (the paper: prompt
-// processing "is usually compute-bound", Section 2.1), so the kernel is organised around MFMA
-// reuse instead of around HBM bytes:
+// With hundreds of request rows per delta the path is a dense contraction (prompt processing is
+// the compute-bound phase of serving, Section 2.1), so the kernel is organised around MFMA reuse
+// instead of around HBM bytes:
 //   * a workgroup (8 waves) owns an output tile of 256 rows of N x 128 request rows (in
 //     delta-sorted order, from the segment pass) and the whole k range -- no split k;
 //   * a wave owns 2 row tiles x 8 column blocks = 16 accumulator tiles (64 registers); W and
 //     packed-delta fragments go from global memory straight into MFMA A operands (each wave owns
 //     its rows, so A needs no sharing), the 128 x 256 slice of x of the current k tile sits in LDS
-//     (double buffered, the next slice is fetched while the current one is multiplied) and every
-//     B fragment read from LDS feeds 2 (dense: 4) MFMAs;
+//     (double buffered; the next slice is fetched in four batches that ride along with the four
+//     base steps, each batch loaded one step before it is stored) and every B fragment read from
+//     LDS feeds 4 dense or 2 sparse MFMAs;
+//   * the order of loads and MFMAs is written out and pinned with scheduling fences: W three
+//     steps ahead, B fragments two column blocks ahead, the next packed tile one delta ahead;
 //   * deltas: contiguous segments of the sorted order; a segment multiplies only the column blocks
-//     it overlaps, and in a block shared with a neighbour the foreign columns of B are zeroed, so
-//     the sparse MFMAs accumulate into the same registers as the base product;
-//   * workgroups are numbered so that the 16 request tiles of one row block run on the same XCD
+//     it overlaps, and in a block shared with a neighbour the lanes of foreign request rows read a
+//     zero row of LDS, so the sparse MFMAs accumulate into the same registers as the base product;
+//   * workgroups are numbered so that the request tiles of one row block run on the same XCD
 //     at the same time and share its L2 copy of the W rows.
+// Measured on the 13B shapes the kernel is bound by the rate at which L2 feeds the CUs (the tile
+// moves 192 KB per 256 k), not by the MFMA pipes.
 #include "dz_mma.h"
 
 namespace {
 
-constexpr int PJ = 8;               // column blocks (16 request rows) per workgroup
-constexpr int PCH = 16 * PJ;        // request rows per workgroup tile
 constexpr int PLDW = 256 + LDS_PAD; // LDS row stride in halfs (one k tile)
 
-template <int BITS, int GROUP, int PR>
-__device__ __forceinline__ void delta_steps_direct(const uint32_t (&st)[PR][Fmt<BITS, GROUP>::SD], const _Float16 *xs,
-                                                   const Geo &g, const int (&brow)[PJ], int sb, int se,
-                                                   f4 (&acc)[PR][PJ])
+// One base step (64 k) for R row tiles x J column blocks.  B fragments are read from LDS two
+// column blocks ahead of the MFMAs that use them: bq holds the fragments of blocks j and j + 1 on
+// entry and, when NEXT is set, those of blocks 0 and 1 of the following step on exit.
+template <int R, int J, bool NEXT>
+__device__ __forceinline__ void base_step(const u32x4 (&buf)[R][2], const _Float16 *xs, const Geo &g,
+                                          const int (&brow)[J], int kofs, f4 (&acc)[R][J], h16 (&bq)[2])
+{
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const h16 b = bq[j & 1];
+        if (j + 2 < J) bq[j & 1] = load_b(xs, brow[j + 2], g, kofs);
+        else if (NEXT) bq[j & 1] = load_b(xs, brow[j + 2 - J], g, kofs + 64);
+        const h8 b0 = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, 6, 7);
+        const h8 b1 = __builtin_shufflevector(b, b, 8, 9, 10, 11, 12, 13, 14, 15);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, buf[r][0]), b0, acc[r][j], 0, 0, 0);
+            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, buf[r][1]), b1, acc[r][j], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);      // keep the reads two blocks ahead of their MFMAs
+    }
+}
+
+// Packed tile (16 rows x 256 k) of R row tiles -> MFMA A operands of the four steps.
+template <int BITS, int GROUP, int R>
+__device__ __forceinline__ void delta_dequant(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], h8 (&av)[4][R],
+                                              uint32_t (&idxw)[2][R])
 {
     typedef Fmt<BITS, GROUP> F;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        h8 av[PR];
-        uint32_t idxw[PR];
+    for (int r = 0; r < R; ++r) {
 #pragma unroll
-        for (int r = 0; r < PR; ++r) {
+        for (int s = 0; s < 4; ++s) {
             const h2 sz2 = as_h2(st[r][F::SC0 + s * F::GPT / 4]);
             const h2 s2 = (h2){sz2.x, sz2.x};
             const h2 z2 = (h2){sz2.y, sz2.y};
             uint32_t w;
-            if (BITS == 4) { w = st[r][s]; idxw[r] = st[r][4 + (s >> 1)]; }
-            else { w = st[r][s >> 1] >> (8 * (s & 1)); idxw[r] = st[r][2 + (s >> 1)]; }
-            av[r] = dequant_step<BITS>(w, s2, z2);
+            if (BITS == 4) w = st[r][s];
+            else w = st[r][s >> 1] >> (8 * (s & 1));
+            av[s][r] = dequant_step<BITS>(w, s2, z2);
         }
+        idxw[0][r] = st[r][(BITS == 4 ? 4 : 2)];
+        idxw[1][r] = st[r][(BITS == 4 ? 4 : 2) + 1];
+    }
+}
+
+// One delta's k tile against the column blocks its segment [sb, se) of the sorted request order
+// overlaps.  A lane whose request row lies outside the segment reads the zero row instead, which
+// removes that column from the product, so the sparse MFMAs can accumulate straight into the
+// registers of the base product.  Blocks outside the segment are skipped by a wave-uniform branch;
+// the four B fragments of a block are reloaded in place for the next overlapped block as soon as
+// the MFMAs of the current one have taken them.
+template <int R, int J>
+__device__ __forceinline__ void delta_mm(const h8 (&av)[4][R], const uint32_t (&idxw)[2][R], const _Float16 *xs,
+                                         int ldw, int zoff, const Geo &g, int sb, int se, f4 (&acc)[R][J])
+{
+    const int j0 = sb >> 4, j1 = (se - 1) >> 4;
+    h16 b[4];
+    {
+        const int pos = 16 * j0 + g.row;
+        const int bo = (pos >= sb && pos < se) ? pos * ldw : zoff;
 #pragma unroll
-        for (int j = 0; j < PJ; ++j) {
-            const int lo = 16 * j, hi = lo + 16;
-            if (hi <= sb || lo >= se) continue;                 // block outside the segment (uniform)
-            h16 b = load_b(xs, brow[j], g, s * 64);
-            if (lo < sb || hi > se) {                           // block shared with a neighbour segment
-                const int pos = lo + g.row;
-                if (!(pos >= sb && pos < se)) {
+        for (int s = 0; s < 4; ++s) b[s] = load_b(xs, bo, g, s * 64);
+    }
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) b[e] = (_Float16)0.f;
-                }
+    for (int j = 0; j < J; ++j) {
+        if (j < j0 || j > j1) continue;                      // wave-uniform
+        const int pos = 16 * min(j + 1, j1) + g.row;         // the last block re-reads itself (unused)
+        const int bn = (pos >= sb && pos < se) ? pos * ldw : zoff;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (s & 1) acc[r][j] = smfmac<1>(av[s][r], b[s], acc[r][j], (int)idxw[s >> 1][r]);
+                else acc[r][j] = smfmac<0>(av[s][r], b[s], acc[r][j], (int)idxw[s >> 1][r]);
             }
-#pragma unroll
-            for (int r = 0; r < PR; ++r) {
-                if (s & 1) acc[r][j] = smfmac<1>(av[r], b, acc[r][j], (int)idxw[r]);
-                else acc[r][j] = smfmac<0>(av[r], b, acc[r][j], (int)idxw[r]);
-            }
+            b[s] = load_b(xs, bn, g, s * 64);
+            __builtin_amdgcn_sched_barrier(0);  // reload right behind the MFMAs that took the fragment
         }
     }
 }
 
-template <int BITS, int GROUP, int PW, int PR, bool HAS_BASE, bool HAS_DELTA>
+template <int BITS, int GROUP, int PW, int PR, int PJ, bool HAS_BASE, bool HAS_DELTA>
 __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int nchunks,
                                                           size_t off_idx, size_t off_scale, size_t blob_total)
 {
     typedef Fmt<BITS, GROUP> F;
     constexpr int SD = F::SD;
     constexpr int THREADS = PW * 64;
-    extern __shared__ __attribute__((aligned(16))) _Float16 xs_all[];     // 2 x [PCH][PLDW]
+    constexpr int PCH = 16 * PJ;            // request rows per workgroup tile
+    extern __shared__ __attribute__((aligned(16))) _Float16 xs_all[];     // 2 x [PCH][PLDW], then one zero row
     __shared__ int s_tok[PCH];
     __shared__ int s_key[PCH];
     __shared__ unsigned long long s_dptr[DZ_MAX_DELTAS];
     __shared__ int s_seg_delta[PCH];
     __shared__ int s_seg_begin[PCH + 1];
-    __shared__ int s_cnt[4];                // starts and valid rows of the first wave, number of segments
+    __shared__ int s_cnt[4];                // segment starts / rows with a delta seen by waves 0 and 1
+    __shared__ int s_nseg;
 
     const int tid = threadIdx.x;
     Geo g;
@@ -126,7 +172,7 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     }
     const unsigned long long sm = __ballot(start);
     const unsigned long long vm = __ballot(valid);
-    if (tid == 0) { s_cnt[0] = __builtin_popcountll(sm); s_cnt[1] = __builtin_popcountll(vm); }
+    if ((tid & 63) == 0 && tid < 128) { s_cnt[wave] = __builtin_popcountll(sm); s_cnt[2 + wave] = __builtin_popcountll(vm); }
     __syncthreads();
     if (HAS_DELTA && tid < PCH) {
         const int base = (tid >= 64) ? s_cnt[0] : 0;
@@ -135,14 +181,14 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
             s_seg_delta[i] = key;
             s_seg_begin[i] = tid;
         }
-        if (tid == 64) {
-            const int ns = s_cnt[0] + __builtin_popcountll(sm);
-            s_cnt[2] = ns;
-            s_seg_begin[ns] = s_cnt[1] + __builtin_popcountll(vm);      // rows that name a delta are a prefix
+        if (tid == 0) {
+            const int ns = s_cnt[0] + (PCH > 64 ? s_cnt[1] : 0);
+            s_nseg = ns;
+            s_seg_begin[ns] = s_cnt[2] + (PCH > 64 ? s_cnt[3] : 0);      // rows that name a delta are a prefix
         }
     }
     __syncthreads();
-    const int nseg = HAS_DELTA ? s_cnt[2] : 0;
+    const int nseg = HAS_DELTA ? s_nseg : 0;
 
     int rtc[PR];
     bool rvalid[PR];
@@ -164,47 +210,52 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
 #pragma unroll
         for (int j = 0; j < PJ; ++j) acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
 
-    const _Float16 *x = (const _Float16 *)a.x;
     const uint32_t w_bytes = (uint32_t)a.N * (uint32_t)a.K * 2u;
     const uint32_t blob_bytes = (uint32_t)blob_total;
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.W ? a.W : a.x, HAS_BASE ? w_bytes : 0u);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (uint32_t)a.T * (uint32_t)a.K * 2u);
 
-    // ---- x slice of one k tile -> LDS buffer: 128 rows x 32 pieces of 16 bytes, 16 per thread,
-    // moved in four batches of four so that a batch can ride along with one MFMA step
-    constexpr int XB = 4096 / THREADS / 4;  // pieces per thread and batch
-    uint4 xv[XB];
-    int xdst[XB];
-#define PF_XLOAD(kt, batch)                                                                                        \
+    // ---- x slice of one k tile -> LDS buffer: PCH rows x 32 pieces of 16 bytes, moved in four
+    // batches so that a batch can ride along with one MFMA step.  Piece p of a thread is row
+    // p * THREADS / 32 + tid / 32, bytes 16 * (tid % 32) of the slice; rows past the end of the
+    // batch get an offset beyond the resource, which the hardware answers with zeros.
+    constexpr int XB = PCH * 32 / THREADS / 4;   // pieces per thread and batch
+    uint32_t xoff[4 * XB];
+#pragma unroll
+    for (int p = 0; p < 4 * XB; ++p) {
+        const int tok = s_tok[p * (THREADS / 32) + (tid >> 5)];
+        xoff[p] = tok >= 0 ? (uint32_t)tok * (uint32_t)a.K * 2u + (uint32_t)(tid & 31) * 16u : 0x80000000u;
+    }
+    const int xdst0 = (tid >> 5) * PLDW + (tid & 31) * 8;
+    u32x4 xvA[XB], xvB[XB];                      // two batches in flight: loaded a step before they are stored
+#define PF_XLOAD(xv, kt, batch)                                                                                    \
     do {                                                                                                           \
-        _Pragma("unroll") for (int u = 0; u < XB; ++u) {                                                          \
-            const int i = ((batch) * XB + u) * THREADS + tid;                                                       \
-            const int rr = i >> 5, cc2 = i & 31;                                                                   \
-            const int tok = s_tok[rr];                                                                             \
-            xdst[u] = rr * PLDW + cc2 * 8;                                                                         \
-            xv[u] = (uint4){0u, 0u, 0u, 0u};                                                                       \
-            if (tok >= 0 && (kt) < g.KT) xv[u] = *(const uint4 *)(x + (size_t)tok * a.K + (size_t)(kt) * 256 + cc2 * 8); \
-        }                                                                                                          \
+        _Pragma("unroll") for (int u = 0; u < XB; ++u)                                                            \
+            xv[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, xoff[(batch) * XB + u], (uint32_t)(kt) * 512u, 0);  \
     } while (0)
-#define PF_XSTORE(buf)                                                                                             \
+#define PF_XSTORE(xv, buf, batch)                                                                                  \
     do {                                                                                                           \
-        _Pragma("unroll") for (int u = 0; u < XB; ++u) *(uint4 *)((buf) + xdst[u]) = xv[u];                       \
+        _Pragma("unroll") for (int u = 0; u < XB; ++u)                                                            \
+            *(u32x4 *)((buf) + xdst0 + ((batch) * XB + u) * (THREADS / 32) * PLDW) = xv[u];                        \
     } while (0)
 
     _Float16 *xcur = xs_all, *xnxt = xs_all + PCH * PLDW;
-#pragma unroll 1
+    const int zoff = 2 * PCH * PLDW;         // the zero row, relative to either buffer's start: see below
+    if (tid < PLDW / 8) *(u32x4 *)(xs_all + zoff + tid * 8) = (u32x4){0u, 0u, 0u, 0u};
+#pragma unroll
     for (int b = 0; b < 4; ++b) {
-        PF_XLOAD(0, b);
-        PF_XSTORE(xcur);
+        PF_XLOAD(xvA, 0, b);
+        PF_XSTORE(xvA, xcur, b);
     }
+    PF_XLOAD(xvA, min(1, g.KT - 1), 0);
 
     u32x4 bwA[PR][2], bwB[PR][2], bwC[PR][2], bwD[PR][2];
-    uint32_t st0[PR][SD], st1[PR][SD];
+    uint32_t st0[PR][SD];
     Cursor ci;                       // next delta tile to fetch: (segment, k tile)
     ci.kt = 0; ci.seg = 0;
     const int ndelta = nseg * g.KT;  // delta tiles this workgroup multiplies
     int ti = 0;
-    // W prefetch distance: three steps when the registers allow it (no deltas), else one
-    constexpr int DIST = HAS_DELTA ? 1 : 3;
+    constexpr int DIST = 3;          // W prefetch distance in steps
     if constexpr (HAS_BASE) {
         base_issue<PR>(rw, wrow, lo.w, 0, bwA);
         if constexpr (DIST == 3) {
@@ -223,55 +274,58 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     __syncthreads();
 
     const int last_step = 4 * g.KT - 1;
-    int parity = 0;
     for (int kt = 0; kt < g.KT; ++kt) {
+        // x slices fetched past the last k tile repeat it and land in the idle buffer
+        const int ktn = min(kt + 1, g.KT - 1), ktnn = min(kt + 2, g.KT - 1);
         // ---- base: four steps of 64 k; each step also moves a quarter of the next x slice
-#define PF_BSTEP(st_, cur, nxt)                                                                                    \
+        h16 bq[2];
+        if constexpr (HAS_BASE) {
+            bq[0] = load_b(xcur, brow[0], g, 0);
+            bq[1] = load_b(xcur, brow[1], g, 0);
+        }
+        // one delta's packed tile: expand it into MFMA operands, request the next tile into the
+        // freed stage buffer, multiply
+#define PF_DSEG(buf, sg_)                                                                                          \
     do {                                                                                                           \
-        PF_XLOAD(kt + 1, st_);                                                                                     \
+        h8 av[4][PR];                                                                                              \
+        uint32_t idxw[2][PR];                                                                                      \
+        delta_dequant<BITS, GROUP, PR>(buf, av, idxw);                                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        PF_DISSUE(buf);                                                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        const int sb = __builtin_amdgcn_readfirstlane(s_seg_begin[sg_]);                                           \
+        const int se = __builtin_amdgcn_readfirstlane(s_seg_begin[(sg_) + 1]);                                     \
+        delta_mm<PR, PJ>(av, idxw, xcur, PLDW, (int)(xs_all + zoff - xcur), g, sb, se, acc);                       \
+    } while (0)
+#define PF_BSTEP(st_, cur, nxt, xcurv, xnxtv)                                                                      \
+    do {                                                                                                           \
+        PF_XLOAD(xnxtv, (st_) < 3 ? ktn : ktnn, ((st_) + 1) & 3);                                                  \
         if constexpr (HAS_BASE) {                                                                                  \
-            base_issue<PR>(rw, wrow, lo.w, min(kt * 4 + (st_) + DIST, last_step), nxt);                               \
-            base_compute<PR, PJ>(cur, xcur, g, brow, (st_) * 64, acc);                                            \
+            base_issue<PR>(rw, wrow, lo.w, min(kt * 4 + (st_) + DIST, last_step), nxt);                            \
+            __builtin_amdgcn_sched_barrier(0);      /* the loads go out before the step's MFMAs */                 \
+            base_step<PR, PJ, ((st_) < 3)>(cur, xcur, g, brow, (st_) * 64, acc, bq);                              \
         }                                                                                                          \
-        PF_XSTORE(xnxt);                                                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        PF_XSTORE(xcurv, xnxt, st_);                                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
     } while (0)
         if constexpr (DIST == 3) {
-            PF_BSTEP(0, bwA, bwD);
-            PF_BSTEP(1, bwB, bwA);
-            PF_BSTEP(2, bwC, bwB);
-            PF_BSTEP(3, bwD, bwC);
+            PF_BSTEP(0, bwA, bwD, xvA, xvB);
+            PF_BSTEP(1, bwB, bwA, xvB, xvA);
+            PF_BSTEP(2, bwC, bwB, xvA, xvB);
+            PF_BSTEP(3, bwD, bwC, xvB, xvA);
         } else {
-            PF_BSTEP(0, bwA, bwB);
-            PF_BSTEP(1, bwB, bwA);
-            PF_BSTEP(2, bwA, bwB);
-            PF_BSTEP(3, bwB, bwA);
+            PF_BSTEP(0, bwA, bwB, xvA, xvB);
+            PF_BSTEP(1, bwB, bwA, xvB, xvA);
+            PF_BSTEP(2, bwA, bwB, xvA, xvB);
+            PF_BSTEP(3, bwB, bwA, xvB, xvA);
         }
 #undef PF_BSTEP
-        // ---- deltas of this k tile, one packed tile per segment, the next one in flight.  The two
-        // stage buffers swap roles whenever a k tile has an odd number of segments.
+        // ---- deltas of this k tile, one packed tile per segment
         if constexpr (HAS_DELTA) {
-#define PF_DELTA(A, B)                                                                                             \
-    do {                                                                                                           \
-        for (int sg = 0; sg < nseg; sg += 2) {                                                                     \
-            {                                                                                                      \
-                PF_DISSUE(B);                                                                                      \
-                const int sb = __builtin_amdgcn_readfirstlane(s_seg_begin[sg]);                                    \
-                const int se = __builtin_amdgcn_readfirstlane(s_seg_begin[sg + 1]);                                \
-                delta_steps_direct<BITS, GROUP, PR>(A, xcur, g, brow, sb, se, acc);                                    \
-            }                                                                                                      \
-            if (sg + 1 < nseg) {                                                                                   \
-                PF_DISSUE(A);                                                                                      \
-                const int sb = __builtin_amdgcn_readfirstlane(s_seg_begin[sg + 1]);                                \
-                const int se = __builtin_amdgcn_readfirstlane(s_seg_begin[sg + 2]);                                \
-                delta_steps_direct<BITS, GROUP, PR>(B, xcur, g, brow, sb, se, acc);                                    \
-            }                                                                                                      \
-        }                                                                                                          \
-    } while (0)
-            if (parity == 0) PF_DELTA(st0, st1);
-            else PF_DELTA(st1, st0);
-            parity ^= (nseg & 1);
-#undef PF_DELTA
+            for (int sg = 0; sg < nseg; ++sg) PF_DSEG(st0, sg);
         }
+#undef PF_DSEG
         lds_barrier();                           // next slice complete, current slice no longer read
         _Float16 *t = xcur; xcur = xnxt; xnxt = t;
     }
@@ -292,11 +346,11 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     }
 }
 
-template <int BITS, int GROUP, int PW, int PR, bool HB, bool HD>
+template <int BITS, int GROUP, int PW, int PR, int PJ, bool HB, bool HD>
 hipError_t launch_pf(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int nchunks, const DzLayout &L, hipStream_t st)
 {
-    auto k = prefill_kernel<BITS, GROUP, PW, PR, HB, HD>;
-    const size_t lds = (size_t)2 * PCH * PLDW * sizeof(_Float16);
+    auto k = prefill_kernel<BITS, GROUP, PW, PR, PJ, HB, HD>;
+    const size_t lds = (size_t)(2 * 16 * PJ + 1) * PLDW * sizeof(_Float16);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -309,22 +363,23 @@ hipError_t launch_pf(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int 
     return hipGetLastError();
 }
 
-template <int PW, int PR, bool HB, bool HD>
+template <int PW, int PR, int PJ, bool HB, bool HD>
 hipError_t launch_pf_fmt(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int nchunks, const DzLayout &L, hipStream_t st)
 {
-    if (!HD || (a.bits == 4 && a.group == 128)) return launch_pf<4, 128, PW, PR, HB, HD>(a, dp, NRB, nchunks, L, st);
-    if (a.bits == 4) return launch_pf<4, 64, PW, PR, HB, HD>(a, dp, NRB, nchunks, L, st);
-    if (a.group == 128) return launch_pf<2, 128, PW, PR, HB, HD>(a, dp, NRB, nchunks, L, st);
-    return launch_pf<2, 64, PW, PR, HB, HD>(a, dp, NRB, nchunks, L, st);
+    if (!HD || (a.bits == 4 && a.group == 128)) return launch_pf<4, 128, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
+    if (a.bits == 4) return launch_pf<4, 64, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
+    if (a.group == 128) return launch_pf<2, 128, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
+    return launch_pf<2, 64, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
 }
 
-template <int PW, int PR>
-hipError_t launch_pf_kind(const DzStreamArgs &a, const DzDeltaPtrs &dp, int nchunks, const DzLayout &L, hipStream_t st)
+template <int PW, int PR, int PJ>
+hipError_t launch_pf_kind(const DzStreamArgs &a, const DzDeltaPtrs &dp, const DzLayout &L, hipStream_t st)
 {
+    const int nchunks = (a.T + 16 * PJ - 1) / (16 * PJ);
     const int NRB = (a.N / 16 + PW * PR - 1) / (PW * PR);
-    if (a.has_base && a.has_delta) return launch_pf_fmt<PW, PR, true, true>(a, dp, NRB, nchunks, L, st);
-    if (a.has_base) return launch_pf_fmt<PW, PR, true, false>(a, dp, NRB, nchunks, L, st);
-    return launch_pf_fmt<PW, PR, false, true>(a, dp, NRB, nchunks, L, st);
+    if (a.has_base && a.has_delta) return launch_pf_fmt<PW, PR, PJ, true, true>(a, dp, NRB, nchunks, L, st);
+    if (a.has_base) return launch_pf_fmt<PW, PR, PJ, true, false>(a, dp, NRB, nchunks, L, st);
+    return launch_pf_fmt<PW, PR, PJ, false, true>(a, dp, NRB, nchunks, L, st);
 }
 
 }  // namespace
@@ -332,12 +387,12 @@ hipError_t launch_pf_kind(const DzStreamArgs &a, const DzDeltaPtrs &dp, int nchu
 int dz_launch_prefill(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &dp, hipStream_t st)
 {
     DzStreamArgs a = args;
-    const int nchunks = (a.T + PCH - 1) / PCH;
     if ((unsigned long long)a.N * a.K * 2ull >= (1ull << 32)) return DZ_ERR_SHAPE;     // 32-bit byte offsets
+    if ((unsigned long long)a.T * a.K * 2ull >= (1ull << 31)) return DZ_ERR_SHAPE;     // x offsets, bit 31 = no row
     DzLayout L = dz_make_layout(a.N, a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
     hipError_t e;
     // 8 waves x 2 row tiles measured faster than 4 x 4 (two waves per SIMD hide each other's waits)
-    if (ctx->wg_waves == 4) e = launch_pf_kind<4, 4>(a, dp, nchunks, L, st);
-    else e = launch_pf_kind<8, 2>(a, dp, nchunks, L, st);
+    if (ctx->wg_waves == 4) e = launch_pf_kind<4, 4, 8>(a, dp, L, st);
+    else e = launch_pf_kind<8, 2, 8>(a, dp, L, st);
     return dz_set_hip_error(ctx, e);
 }
