@@ -10,7 +10,12 @@ with its own weights and deltas resident in HBM (about 34 GB, far beyond the 256
 cache).  Attention, norms, embeddings and sampling are not part of the path.  Inputs are seeded
 and synthetic; no file is read.
 
-Prints ONE JSON line; see the design doc for how each field is derived.
+`--workload` selects the other synthetic configurations (7b_decode_many: 32 deltas, 2-bit, Zipf ids,
+64 rows; 70b_stack: Llama-70B shapes, 4 deltas; 13b_prefill: 2048 request rows in 16 prompt
+segments, which runs the tiled MFMA kernel and is priced against the fp16 MFMA peak instead of HBM).
+
+Prints ONE JSON line.  value = request rows (tokens) per second through the whole stack of layers;
+roofline.achieved = algorithmic bytes (or flops) of all launches of a step / step time.
 """
 from __future__ import annotations
 
@@ -25,6 +30,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
 
 
 def parse():
@@ -32,8 +38,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="7b_decode", choices=["7b_decode", "7b_decode_many", "tiny"])
-    ap.add_argument("--layers", type=int, default=0, help="distinct resident layers (0 = all of the model)")
+    ap.add_argument("--workload", default="7b_decode",
+                    choices=["7b_decode", "7b_decode_many", "13b_prefill", "70b_stack", "tiny"])
+    ap.add_argument("--layers", type=int, default=0,
+                    help="distinct resident layers (0 = all of the model; 4 for 13b_prefill and 8 for 70b_stack, "
+                         "whose full stacks with all deltas would not leave room in 288 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 --pmc counters)")
@@ -55,7 +64,7 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda"
     cfg = S.config(args.workload)
-    n_layers = args.layers if args.layers > 0 else cfg.layers
+    n_layers = args.layers if args.layers > 0 else {"13b_prefill": 4, "70b_stack": 8}.get(cfg.name, cfg.layers)
     projs = S.projections_of(cfg)
     ctx = dz.Context(0)
     nbytes = {(N, K): dz.dz_packed_bytes(N, K, cfg.bits, cfg.group) for _, N, K in projs}
@@ -134,6 +143,16 @@ def main():
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "bytes_per_launch_avg": bytes_per_step // launches_per_step,
                 "avg_launch_us": round(avg_launch_us, 2), "launches_per_step": launches_per_step}
+    if cfg.T > 64:
+        # large batches run the tiled MFMA kernel: 2*T*N*K flops of the base product plus 2*T*N*K/2 of the
+        # 2:4-sparse delta product for every request row that names a delta
+        rows_with_delta = int(((ids >= 0) & (ids < cfg.D)).sum())
+        flops_per_step = n_layers * sum(2.0 * N * K * (cfg.T + 0.5 * rows_with_delta) for _, N, K in projs)
+        tf = flops_per_step / (ms_per_step * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "prefill_kernel (fused base GEMM + SBMM)", "achieved": round(tf, 1),
+                    "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4),
+                    "traffic": None, "flops_per_launch_avg": int(flops_per_step // launches_per_step),
+                    "avg_launch_us": round(avg_launch_us, 2), "launches_per_step": launches_per_step}
 
     cpu = None
     if not args.no_cpu_baseline and host_layer0:
@@ -157,7 +176,8 @@ def main():
                          f"x{cfg.layers} layers"}
 
     line = {
-        "metric": "SBMM+base decode tokens/s and achieved HBM GB/s (% of peak) per layer",
+        "metric": "SBMM+base decode tokens/s and achieved HBM GB/s (% of peak) per layer" if cfg.T <= 64 else
+                  "SBMM+base prefill tokens/s and achieved fp16 MFMA TFLOP/s (% of peak) per layer",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
