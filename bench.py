@@ -44,6 +44,8 @@ def parse():
                     help="distinct resident layers (0 = all of the model; 4 for 13b_prefill and 8 for 70b_stack, "
                          "whose full stacks with all deltas would not leave room in 288 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-group", action="store_true",
+                    help="one dz_linear call per projection instead of one dz_linear_group call for q,k,v and one for gate,up")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 --pmc counters)")
     ap.add_argument("--seed", type=int, default=0)
@@ -97,10 +99,28 @@ def main():
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
-    def step():
+    groups = S.launch_groups(cfg)
+
+    def step_single():
         for row in layers:
             for N, K, W, packed, x, out in row:
                 dz.dz_linear(ctx.h, x, W, packed, d_ids, out, cfg.T, N, K, cfg.bits, cfg.group)
+
+    def step_grouped():
+        # q,k,v read the same activation, so do gate and up: one call each (the x of the group's first
+        # projection stands for the shared input); o and down go alone
+        for row in layers:
+            for gidx in groups:
+                if len(gidx) == 1:
+                    N, K, W, packed, x, out = row[gidx[0]]
+                    dz.dz_linear(ctx.h, x, W, packed, d_ids, out, cfg.T, N, K, cfg.bits, cfg.group)
+                else:
+                    sel = [row[i] for i in gidx]
+                    dz.dz_linear_group(ctx.h, sel[0][4], [r[2] for r in sel], [r[3] for r in sel], d_ids,
+                                       [r[5] for r in sel], cfg.T, [r[0] for r in sel], sel[0][1], cfg.bits, cfg.group)
+
+    grouped = not args.no_group
+    step = step_grouped if grouped else step_single
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -109,26 +129,29 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
-    assert dz.dz_check(ctx.h) == dz.DZ_OK
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    ev0.record()
-    for _ in range(args.steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    ms_total = ev0.elapsed_time(ev1)
-    ms_per_step = ms_total / args.steps
-    assert dz.dz_check(ctx.h) == dz.DZ_OK
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        assert dz.dz_check(ctx.h) == dz.DZ_OK
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(steps):
+            fn()
+        ev1.record()
+        torch.cuda.synchronize()
+        assert dz.dz_check(ctx.h) == dz.DZ_OK
+        return ev0.elapsed_time(ev1) / steps
+
+    ms_per_step = timed(step, args.steps, args.warmup)
+    # the same work as one call per projection, for comparison (not part of `value`)
+    ms_other = timed(step_single if grouped else step_grouped, max(1, args.steps // 2), 1)
 
     # a model pass over the cfg.layers layers: scale if fewer distinct layers were made resident
     ms_model = ms_per_step * cfg.layers / n_layers
     tokens_per_s = cfg.T / (ms_model * 1e-3)
 
-    launches_per_step = n_layers * len(projs)
+    launches_per_step = n_layers * (len(groups) if grouped else len(projs))
     bytes_per_step = n_layers * sum(S.algorithmic_bytes(N, K, cfg.T, cfg.bits, cfg.group, n_active) for _, N, K in projs)
     avg_launch_us = ms_per_step * 1e3 / launches_per_step
     achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
@@ -183,7 +206,10 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": cfg.name, "layers": cfg.layers, "resident_layers": n_layers, "tokens": cfg.T,
                    "deltas": cfg.D, "active_deltas": n_active, "bits": cfg.bits, "group": cfg.group,
-                   "projections_per_layer": len(projs), "gen_seconds": round(gen_s, 1)},
+                   "projections_per_layer": len(projs), "launches_per_layer": len(groups) if grouped else len(projs),
+                   "grouping": "q,k,v in one call; gate,up in one call" if grouped else "one call per projection",
+                   "gen_seconds": round(gen_s, 1)},
+        ("ms_per_step_one_call_per_projection" if grouped else "ms_per_step_grouped"): round(ms_other, 4),
         "hbm_gbs": round(achieved, 1), "hbm_frac_of_peak": round(achieved / HBM_PEAK_GBS, 4),
         "us_per_layer": round(ms_per_step * 1e3 / n_layers, 2),
         "roofline": roofline, "cpu_baseline": cpu,

@@ -246,6 +246,27 @@ def projections_of(cfg: Config) -> List[Tuple[str, int, int]]:
     return out
 
 
+def launch_groups(cfg: Config) -> List[List[int]]:
+    """Indices into projections_of(cfg), grouped by the activation they read: q, k and v read the
+    layer input, gate and up read the attention block's output, o and down read tensors of their
+    own.  Projections of one group can be served by one grouped call."""
+    names = [n for n, _, _ in projections_of(cfg)]
+    first = {"qkvo0": "qkv", "qkvo1": "qkv", "qkvo2": "qkv", "qo0": "qkv", "kv0": "qkv", "kv1": "qkv",
+             "gate_up0": "gate_up", "gate_up1": "gate_up"}
+    groups: Dict[str, List[int]] = {}
+    order: List[List[int]] = []
+    for i, n in enumerate(names):
+        key = first.get(n)
+        if key is None:
+            order.append([i])
+        elif key in groups:
+            groups[key].append(i)
+        else:
+            groups[key] = [i]
+            order.append(groups[key])
+    return order
+
+
 def make_projection(cfg: Config, seed: int, layer: int, name: str, N: int, K: int,
                     device: str = "cpu", with_tables: bool = True) -> Projection:
     """All tensors of one projection, each from its own sub-stream keyed by

@@ -57,6 +57,7 @@ extern "C" {
 #define DZ_ERR_INDEX  (-6)  /* dz_check: some earlier call saw a request index outside [-1, D)       */
 
 #define DZ_MAX_DELTAS 128   /* deltas resident for one call                                          */
+#define DZ_MAX_GROUP  4     /* projections in one dz_linear_group call                               */
 
 typedef struct dz_ctx dz_ctx;
 
@@ -135,6 +136,24 @@ int dz_sbmm(dz_ctx *ctx, const void *x_f16, const void *const *packed_deltas, in
 int dz_linear(dz_ctx *ctx, const void *x_f16, const void *W_f16, const void *const *packed_deltas,
               int D, const int32_t *token_to_delta, void *out_f16, int T, int N, int K, int bits,
               int group, void *stream);
+
+/*
+ * Several linear layers that read the same x for the same requests -- the q, k, v projections of a
+ * transformer layer, or gate and up -- in one call:
+ *   out[p][t] = f16( x[t] . W[p]^T + x[t] . Delta[p][token_to_delta[t]]^T ),   p = 0 .. P-1,
+ * each exactly what dz_linear computes for projection p alone.  The base and delta products of a
+ * layer are independent per output feature (Section 5.1, Eq. (2)), so stacking projections along
+ * the output dimension changes no result; for decode-sized batches (T <= 64) all P projections go
+ * through one kernel launch, which saves the fixed cost of P - 1 launches (Section 5.2 argues the
+ * same way for batching all deltas of a layer into one launch).
+ *   W, out          HOST arrays of P DEVICE pointers; N a HOST array of P output sizes
+ *   packed_deltas   HOST array of P * D DEVICE pointers, projection-major: [p * D + m] is delta m
+ *                   packed for projection p (shape N[p] x K)
+ * All projections share K, bits, group and D.  1 <= P <= DZ_MAX_GROUP and P * D <= 3 * DZ_MAX_DELTAS.
+ */
+int dz_linear_group(dz_ctx *ctx, const void *x_f16, int P, const void *const *W_f16,
+                    const void *const *packed_deltas, int D, const int32_t *token_to_delta,
+                    void *const *out_f16, const int *N, int T, int K, int bits, int group, void *stream);
 
 /* Synchronise `stream`; return DZ_ERR_INDEX if any call since the last dz_check met a request
  * index outside [-1, D) (that request was served with the base model only), else DZ_OK. */

@@ -10,14 +10,15 @@ __all__ = [
     "DZ_OK", "DZ_ERR_ARG", "DZ_ERR_SHAPE", "DZ_ERR_BITS", "DZ_ERR_ALIGN", "DZ_ERR_HIP", "DZ_ERR_INDEX",
     "DZ_MAX_DELTAS", "DzError", "lib", "lib_path", "dz_strerror", "dz_create", "dz_destroy",
     "dz_packed_bytes", "dz_pack_delta", "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm",
-    "dz_linear", "dz_check", "Context", "SYMBOLS",
+    "dz_linear", "dz_linear_group", "dz_check", "Context", "SYMBOLS", "DZ_MAX_GROUP",
 ]
 
 DZ_OK, DZ_ERR_ARG, DZ_ERR_SHAPE, DZ_ERR_BITS, DZ_ERR_ALIGN, DZ_ERR_HIP, DZ_ERR_INDEX = 0, -1, -2, -3, -4, -5, -6
 DZ_MAX_DELTAS = 128
+DZ_MAX_GROUP = 4
 
 SYMBOLS = ["dz_strerror", "dz_last_hip_error", "dz_create", "dz_destroy", "dz_packed_bytes", "dz_pack_delta",
-           "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm", "dz_linear", "dz_check"]
+           "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm", "dz_linear", "dz_linear_group", "dz_check"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _lib = None
@@ -57,6 +58,8 @@ def lib() -> ctypes.CDLL:
         L.dz_base_gemm.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp]
         L.dz_sbmm.argtypes = [vp, vp, ctypes.POINTER(vp), ci, vp, vp, ci, ci, ci, ci, ci, ci, vp]
         L.dz_linear.argtypes = [vp, vp, vp, ctypes.POINTER(vp), ci, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.dz_linear_group.argtypes = [vp, vp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, ctypes.POINTER(vp),
+                                      ctypes.POINTER(ci), ci, ci, ci, ci, vp]
         L.dz_check.argtypes = [vp, vp]
         for name in SYMBOLS:
             getattr(L, name)
@@ -153,6 +156,22 @@ def dz_linear(ctx, x, W, packed_deltas, token_to_delta, out, T, N, K, bits, grou
     rc = lib().dz_linear(ctx, _ptr(x), _ptr(W), arr, D, _ptr(token_to_delta), _ptr(out), T, N, K, bits, group,
                          _stream(stream))
     return _raise(ctx, rc, "dz_linear", check)
+
+
+def dz_linear_group(ctx, x, W_list, packed_deltas_list, token_to_delta, out_list, T, N_list, K, bits, group,
+                    stream=None, check=True) -> int:
+    """W_list, out_list, N_list: one entry per projection; packed_deltas_list: per projection, its D packed deltas."""
+    P = len(W_list)
+    D = len(packed_deltas_list[0]) if P else 0
+    if any(len(d) != D for d in packed_deltas_list) or len(out_list) != P or len(N_list) != P:
+        raise ValueError("dz_linear_group: every projection needs W, out, N and the same number of deltas")
+    warr, _ = _ptr_array(W_list)
+    oarr, _ = _ptr_array(out_list)
+    darr, _ = _ptr_array([d for ds in packed_deltas_list for d in ds])
+    narr = (ctypes.c_int * max(P, 1))(*[int(n) for n in N_list])
+    rc = lib().dz_linear_group(ctx, _ptr(x), P, warr, darr, D, _ptr(token_to_delta), oarr, narr, T, K, bits, group,
+                               _stream(stream))
+    return _raise(ctx, rc, "dz_linear_group", check)
 
 
 def dz_check(ctx, stream=None) -> int:

@@ -224,53 +224,86 @@ int dz_segment(dz_ctx *ctx, const int32_t *ids, int T, int D, int32_t *counts, i
     return dz_launch_segment(ctx, ids, T, D, counts, offsets, perm, nullptr, (hipStream_t)stream);
 }
 
-static int run_linear(dz_ctx *ctx, const void *x, const void *W, const void *const *deltas, int D,
-                      const int32_t *ids, void *out, int T, int N, int K, int bits, int group, int accumulate,
-                      bool has_base, bool has_delta, hipStream_t st)
+// P projections that share x and the request indices.  Small batches: one launch of the streaming
+// kernel for all of them.  Large batches: the tiled kernel, one projection after the other.
+static int run_group(dz_ctx *ctx, const void *x, int P, const void *const *W, const void *const *deltas, int D,
+                     const int32_t *ids, void *const *out, const int *N, int T, int K, int bits, int group,
+                     int accumulate, bool has_base, bool has_delta, hipStream_t st)
 {
-    if (!ctx || T < 0 || D < 0 || D > DZ_MAX_DELTAS) return DZ_ERR_ARG;
-    int rc = check_shape(N, K, bits, group, has_delta);
-    if (rc) return rc;
+    if (!ctx || T < 0 || D < 0 || D > DZ_MAX_DELTAS || P < 1 || P > DZ_MAX_GROUP || !N || !out) return DZ_ERR_ARG;
+    if (has_base && !W) return DZ_ERR_ARG;
+    if (has_delta && P * D > DZ_GROUP_PTRS) return DZ_ERR_ARG;
+    for (int p = 0; p < P; ++p) {
+        int rc = check_shape(N[p], K, bits, group, has_delta);
+        if (rc) return rc;
+    }
     if (T == 0) return DZ_OK;
-    if (!x || !out || (has_base && !W)) return DZ_ERR_ARG;
-    if (has_delta && D > 0 && (!deltas || !ids)) return DZ_ERR_ARG;
-    if (!aligned16(x) || !aligned16(out) || (has_base && !aligned16(W)) || (reinterpret_cast<uintptr_t>(ids) & 3))
-        return DZ_ERR_ALIGN;
-    DzDeltaPtrs dp;
-    memset(&dp, 0, sizeof(dp));
+    if (!x || (has_delta && D > 0 && (!deltas || !ids))) return DZ_ERR_ARG;
+    if (!aligned16(x) || (reinterpret_cast<uintptr_t>(ids) & 3)) return DZ_ERR_ALIGN;
+    for (int p = 0; p < P; ++p) {
+        if (!out[p] || (has_base && !W[p])) return DZ_ERR_ARG;
+        if (!aligned16(out[p]) || (has_base && !aligned16(W[p]))) return DZ_ERR_ALIGN;
+    }
     if (has_delta)
-        for (int m = 0; m < D; ++m) {
+        for (int m = 0; m < P * D; ++m) {
             if (!deltas[m]) return DZ_ERR_ARG;
             if (!aligned16(deltas[m])) return DZ_ERR_ALIGN;
-            dp.p[m] = deltas[m];
         }
     DeviceGuard guard(ctx->device);
     DzStreamArgs a;
     memset(&a, 0, sizeof(a));
-    a.x = x; a.W = W; a.out = out;
-    a.T = T; a.N = N; a.K = K; a.D = D; a.bits = bits; a.group = group;
+    a.x = x;
+    a.T = T; a.K = K; a.D = D; a.bits = bits; a.group = group;
     a.accumulate = accumulate;
     a.has_base = has_base;
     // an SBMM with no deltas still runs (every request gets a zero delta term)
     a.has_delta = has_delta && (D > 0 || !has_base);
     a.err_flag = ctx->err_flag;
-#ifdef DZ_PROF
-    if (!ctx->prof) (void)hipMalloc((void **)&ctx->prof, (size_t)1 << 24);
-    a.prof = ctx->prof;
-#endif
+    const bool tiled = T > 64 && !ctx->no_prefill;      // large batches: MFMA-bound tiled kernel
     if (has_delta && D > 0 && T <= 64) {
         a.ids = ids;                    // small batches are sorted inside the streaming kernel
     } else if (has_delta && D > 0) {
-        rc = ensure_seg(ctx, T, st);
+        int rc = ensure_seg(ctx, T, st);
         if (rc) return rc;
         rc = dz_launch_segment(ctx, ids, T, D, nullptr, nullptr, ctx->seg_perm, ctx->seg_key, st);
         if (rc) return rc;
         a.perm = ctx->seg_perm;
         a.key = ctx->seg_key;
     }
-    // small batches: HBM-bound streaming kernel; large batches: MFMA-bound tiled kernel
-    if (T > 64 && !ctx->no_prefill) return dz_launch_prefill(ctx, a, dp, st);
-    return dz_launch_stream(ctx, a, dp, st);
+    if (!tiled) {                       // small batches: HBM-bound streaming kernel, all projections in one launch
+        DzGroup gp;
+        DzGroupPtrs dp;
+        memset(&gp, 0, sizeof(gp));
+        memset(&dp, 0, sizeof(dp));
+        gp.P = P;
+        for (int p = 0; p < P; ++p) {
+            gp.N[p] = N[p];
+            gp.W[p] = has_base ? W[p] : nullptr;
+            gp.out[p] = out[p];
+        }
+        if (has_delta)
+            for (int m = 0; m < P * D; ++m) dp.p[m] = deltas[m];
+        return dz_launch_stream(ctx, a, gp, dp, st);
+    }
+    for (int p = 0; p < P; ++p) {
+        DzDeltaPtrs dp;
+        memset(&dp, 0, sizeof(dp));
+        if (has_delta)
+            for (int m = 0; m < D; ++m) dp.p[m] = deltas[p * D + m];
+        a.W = has_base ? W[p] : nullptr;
+        a.out = out[p];
+        a.N = N[p];
+        int rc = dz_launch_prefill(ctx, a, dp, st);
+        if (rc) return rc;
+    }
+    return DZ_OK;
+}
+
+static int run_linear(dz_ctx *ctx, const void *x, const void *W, const void *const *deltas, int D,
+                      const int32_t *ids, void *out, int T, int N, int K, int bits, int group, int accumulate,
+                      bool has_base, bool has_delta, hipStream_t st)
+{
+    return run_group(ctx, x, 1, &W, deltas, D, ids, &out, &N, T, K, bits, group, accumulate, has_base, has_delta, st);
 }
 
 int dz_base_gemm(dz_ctx *ctx, const void *x, const void *W, void *out, int T, int N, int K, void *stream)
@@ -291,12 +324,12 @@ int dz_linear(dz_ctx *ctx, const void *x, const void *W, const void *const *delt
     return run_linear(ctx, x, W, deltas, D, ids, out, T, N, K, bits, group, 0, true, true, (hipStream_t)stream);
 }
 
-#ifdef DZ_PROF
-int dz_prof_read(dz_ctx *ctx, void *host, size_t bytes)
+int dz_linear_group(dz_ctx *ctx, const void *x, int P, const void *const *W, const void *const *deltas, int D,
+                    const int32_t *ids, void *const *out, const int *N, int T, int K, int bits, int group,
+                    void *stream)
 {
-    return hipMemcpy(host, ctx->prof, bytes, hipMemcpyDeviceToHost) == hipSuccess ? 0 : -5;
+    return run_group(ctx, x, P, W, deltas, D, ids, out, N, T, K, bits, group, 0, true, true, (hipStream_t)stream);
 }
-#endif
 
 int dz_check(dz_ctx *ctx, void *stream)
 {

@@ -26,14 +26,26 @@ struct dz_ctx {
     int round_tiles;        // DZ_ROUND_TILES
     int no_prefill;         // DZ_NO_PREFILL: serve large batches with the streaming kernel (chunks of 64 rows)
     int wg_waves, wg_rtiles; // DZ_WAVES, DZ_RTILES: workgroup shape of the streaming kernel
-#ifdef DZ_PROF
-    long long *prof;
-#endif
 };
 
 #define DZ_SEG_MAX_D 8192
 
 struct DzDeltaPtrs { const void *p[DZ_MAX_DELTAS]; };
+
+// Several projections that share x and the request indices (q,k,v or gate,up of one transformer
+// layer) can go through the streaming kernel in one launch.  Filled in part by the caller (P, N, W,
+// out) and in part by the launcher.
+#define DZ_GROUP_PTRS (3 * DZ_MAX_DELTAS)       /* projections x deltas of one launch */
+struct DzGroupPtrs { const void *p[DZ_GROUP_PTRS]; };   // packed deltas, projection-major: p[proj * D + delta]
+struct DzGroup {
+    int P;                              // projections (1 .. DZ_MAX_GROUP)
+    int rb_start[DZ_MAX_GROUP + 1];     // first row block of each projection in the concatenated numbering
+    int N[DZ_MAX_GROUP];                // output features of each projection
+    int n_off[DZ_MAX_GROUP];            // first column of each projection in the partial-sum tiles
+    const void *W[DZ_MAX_GROUP];        // [N[p]][K] fp16
+    void *out[DZ_MAX_GROUP];            // [T][N[p]] fp16
+    uint32_t off_idx[DZ_MAX_GROUP], off_scale[DZ_MAX_GROUP], blob_total[DZ_MAX_GROUP];   // packed layout of each projection
+};
 
 // One launch of the streaming kernel (decode-shaped; large T is processed as chunks of 64 rows).
 struct DzStreamArgs {
@@ -44,12 +56,9 @@ struct DzStreamArgs {
     const int32_t *key;         // delta of each sorted position or null (no deltas)
     const int32_t *ids;         // raw request->delta indices: the kernel sorts them itself (T <= 64)
     int32_t *err_flag;
-#ifdef DZ_PROF
-    long long *prof;            // 8 timestamps per workgroup (development builds only)
-#endif
     float *partial;
     int32_t *counters;
-    int T, N, K, D, bits, group;
+    int T, N, K, D, bits, group;   // streaming kernel: N = sum over the projections of the launch
     int accumulate;
     int S;                      // workgroups per chunk of 64 request rows
     int max_slots;              // most workgroups sharing one row block (partial-sum slots)
@@ -63,5 +72,5 @@ int dz_launch_unpack(dz_ctx *, const void *, int, int, int, int, uint8_t *, uint
                      float *, hipStream_t);
 int dz_launch_segment(dz_ctx *, const int32_t *ids, int T, int D, int32_t *counts, int32_t *offsets,
                       int32_t *perm, int32_t *key, hipStream_t);
-int dz_launch_stream(dz_ctx *, const DzStreamArgs &, const DzDeltaPtrs &, hipStream_t);
+int dz_launch_stream(dz_ctx *, const DzStreamArgs &, const DzGroup &, const DzGroupPtrs &, hipStream_t);
 int dz_launch_prefill(dz_ctx *, const DzStreamArgs &, const DzDeltaPtrs &, hipStream_t);

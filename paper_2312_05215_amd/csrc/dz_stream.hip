@@ -34,8 +34,7 @@ namespace {
 
 template <int BITS, int GROUP, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((R == 1 && J <= 2) ? 4 : 2)))
-void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
-                                                            size_t off_idx, size_t off_scale, size_t blob_total)
+void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int round_tiles)
 {
     typedef Fmt<BITS, GROUP> F;
     constexpr int SD = F::SD;
@@ -47,19 +46,13 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
     __shared__ int s_raw[64];
     __shared__ int s_rank[64];
     __shared__ int s_boff[64];              // LDS offset (halfs) of the x row of each sorted position
-    __shared__ unsigned long long s_dptr[DZ_MAX_DELTAS];   // packed-delta pointers (copied from the arguments)
+    __shared__ unsigned long long s_dptr[DZ_GROUP_PTRS];   // packed-delta pointers of every projection (copied from the arguments)
     __shared__ int s_seg_delta[64];
     __shared__ int s_seg_begin[65];
     __shared__ int s_nseg;
     __shared__ int s_last;
 
     const int tid = threadIdx.x;
-#ifdef DZ_PROF
-#define DZ_T(i) do { if (tid == 0) a.prof[(size_t)blockIdx.x * 8 + (i)] = (long long)wall_clock64(); } while (0)
-#else
-#define DZ_T(i) do { } while (0)
-#endif
-    DZ_T(0);
     Geo g;
     g.lane = tid & 63; g.row = g.lane & 15; g.q = g.lane >> 4;
     g.KT = a.K >> 8;
@@ -84,7 +77,6 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
     const int p_end = (int)((long long)(wg + 1) * P / G);
     const int p0 = chunk * 64;
     const int cnt = min(64, a.T - p0);
-    const int RT = a.N >> 4;
 
     // Request order (paper Section 5.2: requests of one delta are grouped).  Batches of up to 64
     // rows are ranked by every workgroup itself from the raw index vector (rank = rows with a
@@ -93,7 +85,10 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
     // Larger batches read the sorted order a segment pass left in the workspace and stage x rows
     // already sorted.
     const bool sort_here = HAS_DELTA && a.ids != nullptr;
-    if (HAS_DELTA && tid < max(a.D, 1)) s_dptr[tid] = tid < a.D ? (unsigned long long)dp.p[tid] : (unsigned long long)a.x;   // before any long-latency load
+    if (HAS_DELTA) {                                               // before any long-latency load
+        for (int i = tid; i < max(gp.P * a.D, 1); i += THREADS)
+            s_dptr[i] = i < gp.P * a.D ? (unsigned long long)dp.p[i] : (unsigned long long)a.x;
+    }
     int my_id = -1;
     if (sort_here && tid < cnt) my_id = a.ids[tid];                 // earliest possible load
     if (!sort_here) {
@@ -111,10 +106,6 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
     }
 
     const _Float16 *x = (const _Float16 *)a.x;
-    const uint32_t w_bytes = (uint32_t)a.N * (uint32_t)a.K * 2u;
-    const uint32_t blob_bytes = (uint32_t)blob_total;
-    const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.W ? a.W : a.x, HAS_BASE ? w_bytes : 0u);
-    _Float16 *out = (_Float16 *)a.out;
     constexpr int AGENT = 0x10;                  // cache-policy bit sc1
     const int Tp = ((a.T + 63) >> 6) << 6;
     const uint32_t slice_bytes = (uint32_t)Tp * (uint32_t)a.N * 4u;
@@ -131,11 +122,24 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
     const int kt0 = p - rb * g.KT;
     const int kt1 = min(g.KT, kt0 + (p_end - p));
     p += kt1 - kt0;
+    // the projection this row block belongs to (a call may carry several projections that share
+    // x: their row blocks are numbered one projection after the other)
+    int pj = 0;
+    while (pj + 1 < gp.P && rb >= gp.rb_start[pj + 1]) ++pj;
+    const int rbl = rb - gp.rb_start[pj];
+    const int Np = gp.N[pj];
+    const int RT = Np >> 4;
+    const int n_off = gp.n_off[pj];
+    const uint32_t off_idx = gp.off_idx[pj], off_scale = gp.off_scale[pj], blob_bytes = gp.blob_total[pj];
+    const __amdgpu_buffer_rsrc_t rw =
+        make_rsrc(HAS_BASE ? gp.W[pj] : a.x, HAS_BASE ? (uint32_t)Np * (uint32_t)a.K * 2u : 0u);
+    _Float16 *out = (_Float16 *)gp.out[pj];
+    const unsigned long long *sd = s_dptr + pj * a.D;
     int rtc[R];
     bool rvalid[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int rt = rb * (WAVES * R) + wave * R + r;
+        const int rt = rbl * (WAVES * R) + wave * R + r;
         rvalid[r] = rt < RT;
         rtc[r] = rvalid[r] ? rt : RT - 1;
     }
@@ -166,7 +170,7 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
         int ti = 0, tc = 0;
 #define DZ_ISSUE(buf)                                                                                              \
     do {                                                                                                           \
-        delta_issue<BITS, GROUP, R>(ci, nd > 0, g, rtc, lo, s_dptr, s_seg_delta, (uint32_t)off_idx, (uint32_t)off_scale, blob_bytes, \
+        delta_issue<BITS, GROUP, R>(ci, nd > 0, g, rtc, lo, sd, s_seg_delta, off_idx, off_scale, blob_bytes,                \
                                     buf);                                                                          \
         if (++ti < nd) advance(ci, kr0, kr1);                                                                      \
     } while (0)
@@ -286,7 +290,6 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
             nd = nseg * ntr;
 #pragma unroll
             for (int j = 0; j < J; ++j) brow[j] = s_boff[16 * j + g.row];
-            DZ_T(1);
         }
         if constexpr (HAS_DELTA) {
             DZ_ISSUE(st0);
@@ -295,7 +298,6 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
         DZ_XSTORE();
         lds_barrier();
         first_round = false;
-        DZ_T(2);
         if constexpr (HAS_BASE) {
             for (int s = 0; s < nsteps; s += 4) {
                 DZ_BSTEP(s, bw0, bw3);
@@ -318,7 +320,6 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
 #undef DZ_XSTORE
     }
 
-    DZ_T(3);
     // ---- results of this segment: lane 16q + c holds rows 4q..4q+3 of the row tile for request
     // column c.  Which workgroups contribute to row block rb follows from the range formula:
     // the owner of flat position f is ceil((f + 1) * G / P) - 1.
@@ -332,7 +333,7 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
 #pragma unroll
             for (int j = 0; j < J; ++j) {
                 const int tok = s_tok[16 * j + g.row];
-                if (tok >= 0) store_row4(out + (size_t)tok * a.N + rtc[r] * 16 + 4 * g.q, acc[r][j], a.accumulate);
+                if (tok >= 0) store_row4(out + (size_t)tok * Np + rtc[r] * 16 + 4 * g.q, acc[r][j], a.accumulate);
             }
         }
         continue;
@@ -352,7 +353,7 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
         for (int j = 0; j < J; ++j) {
             const int pr = 16 * j + g.row;
             if (pr < cnt) {
-                const uint32_t off = ((uint32_t)(p0 + pr) * (uint32_t)a.N + (uint32_t)rtc[r] * 16u + 4u * g.q) * 4u;
+                const uint32_t off = ((uint32_t)(p0 + pr) * (uint32_t)a.N + (uint32_t)(n_off + rtc[r] * 16) + 4u * g.q) * 4u;
                 const u32x4 v = __builtin_bit_cast(u32x4, acc[r][j]);
                 __builtin_amdgcn_raw_buffer_store_b128(v, prs, off, (uint32_t)slot * slice_bytes, AGENT);
             }
@@ -360,7 +361,6 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
     }
     __builtin_amdgcn_s_waitcnt(0);               // this wave's stores have completed
     __syncthreads();
-    DZ_T(4);
     if (tid == 0) {
         int32_t *ctr = a.counters + chunk * NRB + rb;
         const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -369,15 +369,14 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
         s_last = last;
     }
     __syncthreads();
-    DZ_T(5);
     if (s_last) {
         constexpr int width = WAVES * R * 16;        // rows of N per row block
         constexpr int nq = width / 4;
         for (int i = tid; i < cnt * nq; i += THREADS) {
             const int pr = i / nq, c4 = i - pr * nq;
-            const int n = rb * width + c4 * 4;
-            if (n >= a.N) continue;
-            const uint32_t off = ((uint32_t)(p0 + pr) * (uint32_t)a.N + (uint32_t)n) * 4u;
+            const int n = rbl * width + c4 * 4;
+            if (n >= Np) continue;
+            const uint32_t off = ((uint32_t)(p0 + pr) * (uint32_t)a.N + (uint32_t)(n_off + n)) * 4u;
             f4 sum = (f4){0.f, 0.f, 0.f, 0.f};
             for (int s0 = 0; s0 < ncontrib; s0 += 8) {
                 f4 v[8];
@@ -391,61 +390,57 @@ void stream_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int round_tiles,
                     if (s0 + u < ncontrib) sum += v[u];
             }
             const int tok = s_tok[pr];
-            store_row4(out + (size_t)tok * a.N + n, sum, a.accumulate);
+            store_row4(out + (size_t)tok * Np + n, sum, a.accumulate);
         }
     }
-#ifdef DZ_PROF
-    __builtin_amdgcn_s_waitcnt(0);
-    DZ_T(6);
-#endif
   }   // segments
 }
 
 template <int BITS, int GROUP, int WAVES, int R, int J, bool HB, bool HD>
-hipError_t launch_one(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int round_tiles, int grid,
-                      size_t lds, const DzLayout &L, hipStream_t st)
+hipError_t launch_one(const DzStreamArgs &a, const DzGroup &gp, const DzGroupPtrs &dp, int NRB, int round_tiles, int grid,
+                      size_t lds, hipStream_t st)
 {
     auto k = stream_kernel<BITS, GROUP, WAVES, R, J, HB, HD>;
     static bool attr_set = false;       // per instantiation; the attribute is idempotent
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+        hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 8192);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(k, dim3(grid), dim3(WAVES * 64), lds, st, a, dp, NRB, round_tiles, L.off_idx, L.off_scale, L.total);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(WAVES * 64), lds, st, a, gp, dp, NRB, round_tiles);
     return hipGetLastError();
 }
 
 template <int BITS, int GROUP, int WAVES, int R, bool HB, bool HD>
-hipError_t launch_j(int J, const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int rt, int grid, size_t lds,
-                    const DzLayout &L, hipStream_t st)
+hipError_t launch_j(int J, const DzStreamArgs &a, const DzGroup &gp, const DzGroupPtrs &dp, int NRB, int rt, int grid,
+                    size_t lds, hipStream_t st)
 {
     switch (J) {
-    case 1: return launch_one<BITS, GROUP, WAVES, R, 1, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
-    case 2: return launch_one<BITS, GROUP, WAVES, R, 2, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
-    case 3: return launch_one<BITS, GROUP, WAVES, R, 3, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
-    default: return launch_one<BITS, GROUP, WAVES, R, 4, HB, HD>(a, dp, NRB, rt, grid, lds, L, st);
+    case 1: return launch_one<BITS, GROUP, WAVES, R, 1, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
+    case 2: return launch_one<BITS, GROUP, WAVES, R, 2, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
+    case 3: return launch_one<BITS, GROUP, WAVES, R, 3, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
+    default: return launch_one<BITS, GROUP, WAVES, R, 4, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
     }
 }
 
 template <int WAVES, int R, bool HB, bool HD>
-hipError_t launch_fmt(int bits, int group, int J, const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int rt,
-                      int grid, size_t lds, const DzLayout &L, hipStream_t st)
+hipError_t launch_fmt(int bits, int group, int J, const DzStreamArgs &a, const DzGroup &gp, const DzGroupPtrs &dp, int NRB,
+                      int rt, int grid, size_t lds, hipStream_t st)
 {
-    if (!HD) return launch_j<4, 128, WAVES, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
-    if (bits == 4 && group == 128) return launch_j<4, 128, WAVES, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
-    if (bits == 4) return launch_j<4, 64, WAVES, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
-    if (group == 128) return launch_j<2, 128, WAVES, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
-    return launch_j<2, 64, WAVES, R, HB, HD>(J, a, dp, NRB, rt, grid, lds, L, st);
+    if (!HD) return launch_j<4, 128, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
+    if (bits == 4 && group == 128) return launch_j<4, 128, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
+    if (bits == 4) return launch_j<4, 64, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
+    if (group == 128) return launch_j<2, 128, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
+    return launch_j<2, 64, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
 }
 
 template <int WAVES, int R>
-hipError_t launch_kind(const DzStreamArgs &a, int J, const DzDeltaPtrs &dp, int NRB, int rt, int grid, size_t lds,
-                       const DzLayout &L, hipStream_t st)
+hipError_t launch_kind(const DzStreamArgs &a, int J, const DzGroup &gp, const DzGroupPtrs &dp, int NRB, int rt, int grid,
+                       size_t lds, hipStream_t st)
 {
-    if (a.has_base && a.has_delta) return launch_fmt<WAVES, R, true, true>(a.bits, a.group, J, a, dp, NRB, rt, grid, lds, L, st);
-    if (a.has_base) return launch_fmt<WAVES, R, true, false>(a.bits, a.group, J, a, dp, NRB, rt, grid, lds, L, st);
-    return launch_fmt<WAVES, R, false, true>(a.bits, a.group, J, a, dp, NRB, rt, grid, lds, L, st);
+    if (a.has_base && a.has_delta) return launch_fmt<WAVES, R, true, true>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
+    if (a.has_base) return launch_fmt<WAVES, R, true, false>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
+    return launch_fmt<WAVES, R, false, true>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
 }
 
 }  // namespace
@@ -454,10 +449,11 @@ hipError_t launch_kind(const DzStreamArgs &a, int J, const DzDeltaPtrs &dp, int 
 int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st);
 int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
 
-int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &dp, hipStream_t st)
+int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group, const DzGroupPtrs &dp, hipStream_t st)
 {
     DzStreamArgs a = args;
-    const int RT = a.N / 16, KT = a.K / 256;
+    DzGroup gp = group;
+    const int KT = a.K / 256;
     const int nchunks = (a.T + 63) / 64;
     const int J = (a.T >= 64) ? 4 : (a.T + 15) / 16;
     // workgroup shape: few request columns -> 8 waves x 1 row tile (most waves in flight); three or
@@ -465,7 +461,19 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &d
     // which the 2-bit format needs to stay under the LDS bandwidth)
     int WAVES = ctx->wg_waves, R = ctx->wg_rtiles;
     if (WAVES <= 0 || R <= 0) { WAVES = (J <= 2) ? 8 : 4; R = (J <= 2) ? 1 : 2; }
-    const int NRB = (RT + WAVES * R - 1) / (WAVES * R);
+    // row blocks of the projections, one projection after the other; a row block never spans two
+    int NRB = 0, n_total = 0;
+    for (int p = 0; p < gp.P; ++p) {
+        if ((unsigned long long)gp.N[p] * a.K * 2ull >= (1ull << 32)) return DZ_ERR_SHAPE;     // 32-bit byte offsets
+        const DzLayout L = dz_make_layout(gp.N[p], a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
+        gp.off_idx[p] = (uint32_t)L.off_idx; gp.off_scale[p] = (uint32_t)L.off_scale; gp.blob_total[p] = (uint32_t)L.total;
+        gp.rb_start[p] = NRB;
+        gp.n_off[p] = n_total;
+        NRB += (gp.N[p] / 16 + WAVES * R - 1) / (WAVES * R);
+        n_total += gp.N[p];
+    }
+    for (int p = gp.P; p <= DZ_MAX_GROUP; ++p) gp.rb_start[p] = NRB;
+    a.N = n_total;                       // row length of the partial-sum tiles
     const long long units0 = (long long)nchunks * NRB;
     // number of workgroups per chunk: the target (a multiple of the CU count) unless the call has
     // fewer (row block, k tile) positions than that
@@ -500,11 +508,9 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &d
     a.counters = ctx->counters;
     const long long grid = (long long)nchunks * G;
     if (grid > 0x7fffffffLL) return DZ_ERR_SHAPE;
-    if ((unsigned long long)a.N * a.K * 2ull >= (1ull << 32)) return DZ_ERR_SHAPE;     // 32-bit byte offsets
-    DzLayout L = dz_make_layout(a.N, a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
     hipError_t e;
-    if (WAVES == 8 && R == 1) e = launch_kind<8, 1>(a, J, dp, NRB, round_tiles, (int)grid, lds, L, st);
-    else if (WAVES == 8 && R == 2) e = launch_kind<8, 2>(a, J, dp, NRB, round_tiles, (int)grid, lds, L, st);
-    else e = launch_kind<4, 2>(a, J, dp, NRB, round_tiles, (int)grid, lds, L, st);
+    if (WAVES == 8 && R == 1) e = launch_kind<8, 1>(a, J, gp, dp, NRB, round_tiles, (int)grid, lds, st);
+    else if (WAVES == 8 && R == 2) e = launch_kind<8, 2>(a, J, gp, dp, NRB, round_tiles, (int)grid, lds, st);
+    else e = launch_kind<4, 2>(a, J, gp, dp, NRB, round_tiles, (int)grid, lds, st);
     return dz_set_hip_error(ctx, e);
 }
