@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-group", action="store_true",
                     help="one dz_linear call per projection instead of one dz_linear_group call for q,k,v and one for gate,up")
+    ap.add_argument("--no-compare", action="store_true",
+                    help="skip the extra timing of the other launch grouping (keeps a profile of the run to one kind of launch)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 --pmc counters)")
     ap.add_argument("--seed", type=int, default=0)
@@ -145,7 +147,7 @@ def main():
 
     ms_per_step = timed(step, args.steps, args.warmup)
     # the same work as one call per projection, for comparison (not part of `value`)
-    ms_other = timed(step_single if grouped else step_grouped, max(1, args.steps // 2), 1)
+    ms_other = None if args.no_compare else timed(step_single if grouped else step_grouped, max(1, args.steps // 2), 1)
 
     # a model pass over the cfg.layers layers: scale if fewer distinct layers were made resident
     ms_model = ms_per_step * cfg.layers / n_layers
@@ -155,12 +157,18 @@ def main():
     bytes_per_step = n_layers * sum(S.algorithmic_bytes(N, K, cfg.T, cfg.bits, cfg.group, n_active) for _, N, K in projs)
     avg_launch_us = ms_per_step * 1e3 / launches_per_step
     achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
-    traffic = None      # measured HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, see profiles/)
+    # measured HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/);
+    # only quoted when the run launches the way the profiled run did
+    traffic = None
     try:
+        prof = {}
         for ln in open(os.path.join(ROOT, "profiles", "stream_kernel_7b_decode_pmc.txt")):
-            if ln.startswith("traffic_bytes_per_launch:") and cfg.name == "7b_decode":
-                traffic = int(ln.split(":")[1])
-    except OSError:
+            if ln.startswith("traffic_"):
+                k, v = ln.split(":")
+                prof[k] = int(v)
+        if cfg.name == "7b_decode" and prof.get("traffic_launches_per_layer") == launches_per_step // n_layers:
+            traffic = prof.get("traffic_bytes_per_launch")
+    except (OSError, ValueError):
         pass
     roofline = {"bound": "hbm", "kernel": "stream_kernel (fused base GEMM + SBMM)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
@@ -209,7 +217,8 @@ def main():
                    "projections_per_layer": len(projs), "launches_per_layer": len(groups) if grouped else len(projs),
                    "grouping": "q,k,v in one call; gate,up in one call" if grouped else "one call per projection",
                    "gen_seconds": round(gen_s, 1)},
-        ("ms_per_step_one_call_per_projection" if grouped else "ms_per_step_grouped"): round(ms_other, 4),
+        ("ms_per_step_one_call_per_projection" if grouped else "ms_per_step_grouped"):
+            None if ms_other is None else round(ms_other, 4),
         "hbm_gbs": round(achieved, 1), "hbm_frac_of_peak": round(achieved / HBM_PEAK_GBS, 4),
         "us_per_layer": round(ms_per_step * 1e3 / n_layers, 2),
         "roofline": roofline, "cpu_baseline": cpu,
