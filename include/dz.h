@@ -71,17 +71,17 @@ int dz_create(dz_ctx **ctx, int device);
 int dz_destroy(dz_ctx *ctx);
 
 /*
- * Size in bytes of one packed delta: the kept values' codes, their 2-bit positions (Section 4.1
- * step 2: "non-zero values ... and their 2-bit indices"; step 3: 32/b codes per 32-bit word) and
- * one fp16 (scale, zero) pair per row and group:
+ * Size in bytes of one packed delta: the kept values' codes, their 2-bit positions (Section 4.1:
+ * step 2 keeps the non-zero values with a 2-bit position each, step 3 puts 32/b codes in a 32-bit
+ * word) and one fp16 (scale, zero) pair per row and group:
  *     N*K*(2*bits + 4)/32  +  4*N*K/group.
  * Returns 0 for shapes the library does not accept.
  */
 size_t dz_packed_bytes(int N, int K, int bits, int group);
 
 /*
- * Lay one delta's canonical tables out in the order the kernels stream them (Algorithm 1, "pack
- * and store").  All pointers DEVICE; codes/idx need no alignment beyond 1, scale/zero 2 bytes;
+ * Lay one delta's canonical tables out in the order the kernels stream them (the packing step that
+ * ends Algorithm 1).  All pointers DEVICE; codes/idx need no alignment beyond 1, scale/zero 2 bytes;
  * packed_out is caller-allocated, dz_packed_bytes() long, 16-byte aligned.  The packed layout is
  * private to the library but position independent: the bytes may be saved, copied and reloaded.
  * Table contents are not validated; codes are masked to `bits`, positions to 2 bits.

@@ -1,5 +1,5 @@
 // dz_pack_delta / dz_unpack_delta kernels: canonical tables <-> streaming layout (dz_layout.h).
-// Off the per-token path (run once per delta, Algorithm 1 "pack and store"), so these are plain
+// Off the per-token path (run once per delta, the packing step that ends Algorithm 1), so these are plain
 // gather kernels: one thread per packed dword (pack) or per group of four (unpack).
 #include "dz_internal.h"
 

@@ -3,14 +3,13 @@
 //   out[t] = f16( x[t] . W^T + x[t] . Delta_{Idx[t]}^T )      (paper Section 5.1 Eq. (2); Section 5.2)
 //
 // Decode is bound by the bytes of W and of the packed deltas that must cross HBM once per call
-// (Section 5.1: "decoding latency is proportional to the GPU memory consumption of the model
-// weights"), so the kernel is organised around streaming those bytes exactly once with 16-byte
-// loads per lane, and keeping everything else (x, dequantisation, 2:4 expansion, the merge of base
-// and delta results) on chip:
+// (Section 5.1: decode latency follows the memory footprint of the weights), so the kernel is
+// organised around streaming those bytes exactly once with 16-byte loads per lane, and keeping
+// everything else (x, dequantisation, 2:4 expansion, the merge of base and delta results) on chip:
 //
-//   * a workgroup (4 waves) owns a block of 4*R row tiles (16 rows each) and one slice of k;
-//     its slice of x -- rows already in delta-sorted order -- sits in LDS and is the B operand
-//     of every MFMA; request rows are the MFMA N dimension, 16 per column block;
+//   * a workgroup (8 or 4 waves) owns a block of WAVES*R row tiles (16 rows each) and one slice of
+//     k; its slice of x sits in LDS and is the B operand of every MFMA; request rows are the MFMA
+//     N dimension, 16 per column block, in delta-sorted order;
 //   * base: W fragments go from global memory straight into the A operand of
 //     V_MFMA_F32_16X16X32_F16 (lane 16q+r holds W[r][8q..8q+7], one 16-byte load);
 //   * deltas: for each delta that has requests in the batch (segments of the sorted order; deltas
@@ -22,12 +21,15 @@
 //     segment's accumulator is merged;
 //   * split-k partial sums meet in fp32: every workgroup stores its partial tile, the last one to
 //     arrive for a row block (an arrival counter) adds them in fixed order and rounds to fp16
-//     once.  With one slice the result is rounded and stored directly.
+//     once.  With one slice the result is rounded and stored directly;
+//   * several projections that read the same x (q,k,v or gate,up of a transformer layer) can share
+//     one launch: their row blocks are numbered one projection after the other and each piece of
+//     work looks up its projection's W, packed deltas and output.
 //
 // The paper's kernel launches per-delta child kernels from a parent kernel; HIP has no device-side
 // launch, so "one launch for all deltas" is a loop over the batch's segment list inside each
-// workgroup.  Larger T is served as chunks of 64 sorted rows (grid dimension), which re-reads the
-// weights from cache per chunk.
+// workgroup.  Batches of more than 64 rows normally go to the tiled kernel; when they are sent
+// here they run as chunks of 64 sorted rows (a grid dimension).
 #include "dz_mma.h"
 
 namespace {
