@@ -202,100 +202,6 @@ __device__ __forceinline__ void delta_issue(const Cursor &c, bool valid, const G
     }
 }
 
-// The four steps of one packed tile against column blocks j0 .. j0 + C - 1.
-template <int BITS, int GROUP, int R, int J, int C>
-__device__ __forceinline__ void delta_steps(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], const _Float16 *xs,
-                                            const Geo &g, int kofs, const int (&boff)[C], f4 (&tmp)[R][J])
-{
-    typedef Fmt<BITS, GROUP> F;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        h8 av[R];
-        uint32_t idxw[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const h2 sz2 = as_h2(st[r][F::SC0 + s * F::GPT / 4]);
-            const h2 s2 = (h2){sz2.x, sz2.x};
-            const h2 z2 = (h2){sz2.y, sz2.y};
-            uint32_t w;
-            if (BITS == 4) { w = st[r][s]; idxw[r] = st[r][4 + (s >> 1)]; }
-            else { w = st[r][s >> 1] >> (8 * (s & 1)); idxw[r] = st[r][2 + (s >> 1)]; }
-            av[r] = dequant_step<BITS>(w, s2, z2);
-        }
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            const h16 b = load_b(xs, boff[c], g, kofs + s * 64);
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (s & 1) tmp[r][c] = smfmac<1>(av[r], b, tmp[r][c], (int)idxw[r]);
-                else tmp[r][c] = smfmac<0>(av[r], b, tmp[r][c], (int)idxw[r]);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);      // keep one step's operands live at a time
-    }
-}
-
-template <int BITS, int GROUP, int R, int J>
-__device__ __forceinline__ void delta_compute(const Cursor &c, int kr0, int kr1,
-                                              const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], const _Float16 *xs,
-                                              const Geo &g, const int *s_seg_begin, const int *s_boff,
-                                              f4 (&acc)[R][J], f4 (&tmp)[R][J])
-{
-    const int sb = __builtin_amdgcn_readfirstlane(s_seg_begin[c.seg]);
-    const int se = __builtin_amdgcn_readfirstlane(s_seg_begin[c.seg + 1]);
-    const int j0 = sb >> 4;
-    const int C = ((se - 1) >> 4) - j0 + 1;
-    if (c.kt == kr0) {
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int j = 0; j < J; ++j) tmp[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
-    }
-    const int kofs = (c.kt - kr0) * 256;
-    // LDS rows of this lane's request column in each overlapped block
-    int boff[J];
-#pragma unroll
-    for (int cc = 0; cc < J; ++cc) boff[cc] = s_boff[min(16 * (j0 + cc), 48) + g.row];
-    if (C == 1) {
-        const int b1[1] = {boff[0]};
-        delta_steps<BITS, GROUP, R, J, 1>(st, xs, g, kofs, b1, tmp);
-    }
-    if constexpr (J >= 2) {
-        if (C == 2) {
-            const int b2[2] = {boff[0], boff[1]};
-            delta_steps<BITS, GROUP, R, J, 2>(st, xs, g, kofs, b2, tmp);
-        }
-    }
-    if constexpr (J >= 3) {
-        if (C == 3) {
-            const int b3[3] = {boff[0], boff[1], boff[2]};
-            delta_steps<BITS, GROUP, R, J, 3>(st, xs, g, kofs, b3, tmp);
-        }
-    }
-    if constexpr (J >= 4) {
-        if (C == 4) {
-            const int b4[4] = {boff[0], boff[1], boff[2], boff[3]};
-            delta_steps<BITS, GROUP, R, J, 4>(st, xs, g, kofs, b4, tmp);
-        }
-    }
-    if (c.kt == kr1 - 1) {
-        // merge: only the columns (sorted positions) that belong to this segment
-#pragma unroll
-        for (int cc = 0; cc < J; ++cc) {
-            const int pos = 16 * (j0 + cc) + g.row;
-            const bool in = cc < C && pos >= sb && pos < se;
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                f4 t = tmp[r][cc];
-                if (!in) t = (f4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < J; ++j)
-                    if (j == j0 + cc) acc[r][j] += t;
-            }
-        }
-    }
-}
-
 __device__ __forceinline__ void advance(Cursor &c, int kr0, int kr1)
 {
     if (++c.kt == kr1) { c.kt = kr0; ++c.seg; }

@@ -34,6 +34,121 @@
 
 namespace {
 
+// ---- delta phase of the streaming kernel -------------------------------------------------------
+// A task = one packed tile (16 rows x 256 k per row tile) of one delta segment.  What a task needs
+// to know about its segment -- the blob pointer and the range [sb, se) of sorted positions -- sits
+// in registers, segment i in lane i, and is fetched with a lane read: no LDS round trip stands
+// between a task and its loads.
+struct SegTable {
+    uint32_t plo, phi;      // packed-delta blob of the segment's delta (for the current projection)
+    int sb, se;             // sorted positions [sb, se)
+};
+
+template <int J>
+struct Task {
+    int boff[J];            // per lane and column block: LDS offset (halfs) of the x row it multiplies,
+                            // the zero row if its sorted position is not in the segment
+    int kofs;               // offset of the task's k tile in the LDS slice (halfs)
+};
+
+template <int J>
+__device__ __forceinline__ void task_setup(const Cursor &c, int kr0, const SegTable &tab, const int (&brow)[J], int zoff,
+                                           const Geo &g, Task<J> &t)
+{
+    const int sb = __builtin_amdgcn_readlane(tab.sb, c.seg);
+    const int se = __builtin_amdgcn_readlane(tab.se, c.seg);
+    t.kofs = (c.kt - kr0) * 256;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int pos = 16 * j + g.row;
+        t.boff[j] = (pos >= sb && pos < se) ? brow[j] : zoff;
+    }
+}
+
+// B fragments of step s of a task, all column blocks (a block the segment does not touch reads
+// the zero row in every lane and adds nothing: with at most four blocks that costs less than the
+// branches and register copies a per-block skip would put between the MFMAs).
+template <int J>
+__device__ __forceinline__ void task_frags(const Task<J> &t, const _Float16 *xs, const Geo &g, int s, h16 (&b)[J])
+{
+#pragma unroll
+    for (int j = 0; j < J; ++j) b[j] = load_b(xs, t.boff[j], g, t.kofs + s * 64);
+}
+
+template <int BITS, int GROUP, int R>
+__device__ __forceinline__ void stream_delta_issue(const Cursor &c, bool valid, const Geo &g, const int (&rtc)[R],
+                                                   const LaneOffs &lo, const SegTable &tab, uint32_t off_idx,
+                                                   uint32_t off_scale, uint32_t blob_bytes,
+                                                   uint32_t (&st)[R][Fmt<BITS, GROUP>::SD])
+{
+    typedef Fmt<BITS, GROUP> F;
+    // With no task left the loads are still issued (so the load count never depends on a branch)
+    // but against an empty resource: the hardware returns zeros and touches no memory.
+    const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)tab.plo, c.seg);
+    const uint32_t h = (uint32_t)__builtin_amdgcn_readlane((int)tab.phi, c.seg);
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc((const void *)(((unsigned long long)h << 32) | l), valid ? blob_bytes : 0u);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint32_t tile = (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)c.kt;
+        const uint32_t sc = off_scale + tile * (16u * F::GPT * 4u);
+        const u32x4 x0 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.c, tile * 1024u, 0);
+        st[r][0] = x0.x; st[r][1] = x0.y; st[r][2] = x0.z; st[r][3] = x0.w;
+        if constexpr (BITS == 4) {
+            const u32x2 x1 = __builtin_amdgcn_raw_buffer_load_b64(rs, lo.i, off_idx + tile * 512u, 0);
+            st[r][4] = x1.x; st[r][5] = x1.y;
+        }
+        if constexpr (F::GPT == 2) {
+            const u32x2 x2 = __builtin_amdgcn_raw_buffer_load_b64(rs, lo.s, sc, 0);
+            st[r][F::SC0] = x2.x; st[r][F::SC0 + 1] = x2.y;
+        } else {
+            const u32x4 x2 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.s, sc, 0);
+            st[r][F::SC0] = x2.x; st[r][F::SC0 + 1] = x2.y; st[r][F::SC0 + 2] = x2.z; st[r][F::SC0 + 3] = x2.w;
+        }
+    }
+}
+
+// The four steps of task `t` (stage registers st) accumulated straight into acc: lanes of request
+// rows outside the segment multiply the zero row.  b0 holds the fragments of step 0 on entry; each
+// step first sends out the LDS reads of the next step -- after step 3 those of step 0 of the next
+// task `tn` -- so that a read is never waited for right after it is issued.  The two fragment
+// buffers alternate; after four steps b0 is the live one again.
+template <int BITS, int GROUP, int R, int J>
+__device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], const Task<J> &t,
+                                                  const Task<J> &tn, const _Float16 *xs, const Geo &g, h16 (&b0)[J],
+                                                  h16 (&b1)[J], f4 (&acc)[R][J])
+{
+    typedef Fmt<BITS, GROUP> F;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        if (s == 0) task_frags<J>(t, xs, g, 1, b1);
+        else if (s == 1) task_frags<J>(t, xs, g, 2, b0);
+        else if (s == 2) task_frags<J>(t, xs, g, 3, b1);
+        else task_frags<J>(tn, xs, g, 0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        h8 av[R];
+        uint32_t idxw[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const h2 sz2 = as_h2(st[r][F::SC0 + s * F::GPT / 4]);
+            const h2 s2 = (h2){sz2.x, sz2.x};
+            const h2 z2 = (h2){sz2.y, sz2.y};
+            uint32_t w;
+            if (BITS == 4) { w = st[r][s]; idxw[r] = st[r][4 + (s >> 1)]; }
+            else { w = st[r][s >> 1] >> (8 * (s & 1)); idxw[r] = st[r][2 + (s >> 1)]; }
+            av[r] = dequant_step<BITS>(w, s2, z2);
+        }
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (s & 1) acc[r][j] = smfmac<1>(av[r], b1[j], acc[r][j], (int)idxw[r]);
+                else acc[r][j] = smfmac<0>(av[r], b0[j], acc[r][j], (int)idxw[r]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 template <int BITS, int GROUP, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((R == 1 && J <= 2) ? 4 : 2)))
 void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int round_tiles)
@@ -42,6 +157,12 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     constexpr int SD = F::SD;
     constexpr int THREADS = WAVES * 64;
     constexpr int ZROW = 16 * J;            // an all-zero LDS row for column slots without a request
+#ifndef DZ_DSTG_SMALL
+#define DZ_DSTG_SMALL 3
+#endif
+    // packed-tile stage buffers of the delta phase (DSTG - 1 tiles in flight): as many as the
+    // register budget of the shape's occupancy allows
+    constexpr int DSTG = (R == 1 && J <= 2) ? DZ_DSTG_SMALL : 5;
     extern __shared__ __attribute__((aligned(16))) _Float16 xs[];     // [16J + 1][LDW]
     __shared__ int s_tok[64];               // request row of each sorted position (-1: none)
     __shared__ int s_key[64];               // delta of each sorted position
@@ -107,7 +228,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         lds_barrier();
     }
 
-    const _Float16 *x = (const _Float16 *)a.x;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (uint32_t)a.T * (uint32_t)a.K * 2u);
     constexpr int AGENT = 0x10;                  // cache-policy bit sc1
     const int Tp = ((a.T + 63) >> 6) << 6;
     const uint32_t slice_bytes = (uint32_t)Tp * (uint32_t)a.N * 4u;
@@ -145,14 +266,11 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         rvalid[r] = rt < RT;
         rtc[r] = rvalid[r] ? rt : RT - 1;
     }
-    f4 acc[R][J], tmp[R][J];
+    f4 acc[R][J];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int j = 0; j < J; ++j) {
-            acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
-            tmp[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
-        }
+        for (int j = 0; j < J; ++j) acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
     for (int kr0 = kt0; kr0 < kt1; kr0 += round_tiles) {
         const int kr1 = min(kt1, kr0 + round_tiles);
         const int ntr = kr1 - kr0;
@@ -164,7 +282,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         // named stage buffers (so each stays in registers), rotated by hand.  Issue cursors stop at
         // the last task / step and re-issue it (a few redundant cache hits at the end of a round)
         // so that issuing needs no branch.
-        uint32_t st0[R][SD], st1[R][SD], st2[R][SD];
+        uint32_t st0[R][SD], st1[R][SD], st2[R][SD], st3[R][SD], st4[R][SD];
         u32x4 bw0[R][2], bw1[R][2], bw2[R][2], bw3[R][2];
         uint32_t wbase[R];
 #pragma unroll
@@ -172,16 +290,20 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         int ti = 0, tc = 0;
 #define DZ_ISSUE(buf)                                                                                              \
     do {                                                                                                           \
-        delta_issue<BITS, GROUP, R>(ci, nd > 0, g, rtc, lo, sd, s_seg_delta, off_idx, off_scale, blob_bytes,                \
-                                    buf);                                                                          \
+        stream_delta_issue<BITS, GROUP, R>(ci, nd > 0, g, rtc, lo, tab, off_idx, off_scale, blob_bytes, buf);      \
         if (++ti < nd) advance(ci, kr0, kr1);                                                                      \
     } while (0)
 #define DZ_STEP(cur, nxt)                                                                                          \
     do {                                                                                                           \
         DZ_ISSUE(nxt);                                                                                             \
         if (tc < nd) {                                                                                             \
-            delta_compute<BITS, GROUP, R, J>(cc, kr0, kr1, cur, xs, g, s_seg_begin, s_boff, acc, tmp);             \
-            advance(cc, kr0, kr1);                                                                                 \
+            Cursor cn = cc;                                                                                        \
+            if (tc + 1 < nd) advance(cn, kr0, kr1);     /* after the last task: the same one again, unused */     \
+            Task<J> tn;                                                                                            \
+            task_setup<J>(cn, kr0, tab, brow, ZROW * g.LDW, g, tn);                                                \
+            stream_delta_task<BITS, GROUP, R, J>(cur, tk, tn, xs, g, bq, bq1, acc);                                     \
+            tk = tn;                                                                                               \
+            cc = cn;                                                                                               \
         }                                                                                                          \
         ++tc;                                                                                                      \
     } while (0)
@@ -197,8 +319,11 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         const int cpr = ntr * 32;                // 16-byte pieces per row
         const int npieces = 16 * J * cpr;
         const uint32_t rcp = (65536u + (uint32_t)ntr - 1u) / (uint32_t)ntr;
-        constexpr int XB = 2;                    // x pieces per thread and batch
-        uint4 xv[XB];
+        // two batches of loads per thread cover the largest round: the first is written to LDS
+        // right away, the second stays in registers while the weight prefetch is issued behind it
+        // (one batch for the whole slice would not fit the registers next to that prefetch)
+        constexpr int XB = (16 * J * ((J <= 2) ? 4 : 2) * 32 + 2 * THREADS - 1) / (2 * THREADS);
+        u32x4 xv[XB];
         int xdst[XB];
 #define DZ_XLOAD(i0)                                                                                               \
     do {                                                                                                           \
@@ -209,17 +334,17 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             int tok = -1;                                                                                          \
             if (i < npieces) tok = sort_here ? (rr < cnt ? rr : -1) : s_tok[rr];                                   \
             xdst[u] = (i < npieces) ? rr * g.LDW + cc2 * 8 : -1;                                                   \
-            xv[u] = (uint4){0u, 0u, 0u, 0u};                                                                       \
-            if (tok >= 0) xv[u] = *(const uint4 *)(x + (size_t)tok * a.K + (size_t)kr0 * 256 + cc2 * 8);          \
+            /* a row that does not exist gets an offset beyond the resource and reads zeros */                     \
+            const uint32_t xo = tok >= 0 ? (uint32_t)tok * (uint32_t)a.K * 2u + (uint32_t)kr0 * 512u + (uint32_t)cc2 * 16u \
+                                         : 0xFFFFFFF0u;                                                            \
+            xv[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, xo, 0, 0);                                           \
         }                                                                                                          \
     } while (0)
 #define DZ_XSTORE()                                                                                                \
     do {                                                                                                           \
         _Pragma("unroll") for (int u = 0; u < XB; ++u)                                                            \
-            if (xdst[u] >= 0) *(uint4 *)(xs + xdst[u]) = xv[u];                                                    \
+            if (xdst[u] >= 0) *(u32x4 *)(xs + xdst[u]) = xv[u];                                                    \
     } while (0)
-        // all batches but the last go to LDS right away (nothing else is in flight yet); the last
-        // batch stays in registers while the weight prefetch is issued behind it
         int xb0 = 0;
         for (; xb0 + THREADS * XB < npieces; xb0 += THREADS * XB) {
             DZ_XLOAD(xb0 + tid);
@@ -293,9 +418,17 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
 #pragma unroll
             for (int j = 0; j < J; ++j) brow[j] = s_boff[16 * j + g.row];
         }
+        SegTable tab = {0u, 0u, 0, 0};
         if constexpr (HAS_DELTA) {
+            if (g.lane < nseg) {                    // segment table: segment i in lane i
+                const unsigned long long bp = sd[s_seg_delta[g.lane]];
+                tab.plo = (uint32_t)bp; tab.phi = (uint32_t)(bp >> 32);
+                tab.sb = s_seg_begin[g.lane]; tab.se = s_seg_begin[g.lane + 1];
+            }
             DZ_ISSUE(st0);
             DZ_ISSUE(st1);
+            if constexpr (DSTG >= 4) DZ_ISSUE(st2);
+            if constexpr (DSTG >= 5) DZ_ISSUE(st3);
         }
         DZ_XSTORE();
         lds_barrier();
@@ -309,10 +442,27 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             }
         }
         if constexpr (HAS_DELTA) {
+            Task<J> tk;
+            h16 bq[J], bq1[J];
+            task_setup<J>(cc, kr0, tab, brow, ZROW * g.LDW, g, tk);
+            task_frags<J>(tk, xs, g, 0, bq);
             while (tc < nd) {
-                DZ_STEP(st0, st2);
-                DZ_STEP(st1, st0);
-                DZ_STEP(st2, st1);
+                if constexpr (DSTG == 3) {
+                    DZ_STEP(st0, st2);
+                    DZ_STEP(st1, st0);
+                    DZ_STEP(st2, st1);
+                } else if constexpr (DSTG == 4) {
+                    DZ_STEP(st0, st3);
+                    DZ_STEP(st1, st0);
+                    DZ_STEP(st2, st1);
+                    DZ_STEP(st3, st2);
+                } else {
+                    DZ_STEP(st0, st4);
+                    DZ_STEP(st1, st0);
+                    DZ_STEP(st2, st1);
+                    DZ_STEP(st3, st2);
+                    DZ_STEP(st4, st3);
+                }
             }
         }
 #undef DZ_ISSUE
@@ -492,6 +642,7 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group
     }
     const size_t Tp = (size_t)nchunks * 64;
     if ((size_t)max_slots * Tp * a.N * 4 >= ((size_t)1 << 32)) return DZ_ERR_SHAPE;    // 32-bit byte offsets
+    if ((unsigned long long)a.T * a.K * 2ull >= 0xFFFFFFF0ull) return DZ_ERR_SHAPE;
     // one batch of x loads per thread must cover a round (see XB in the kernel)
     const int round_cap = (J <= 2 ? 4 : 2);
     int round_tiles = (ctx->round_tiles > 0 && ctx->round_tiles < round_cap) ? ctx->round_tiles : round_cap;
