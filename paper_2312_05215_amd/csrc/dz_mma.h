@@ -39,6 +39,15 @@ __device__ __forceinline__ f4 smfmac(h8 a, h16 b, f4 c, int idx)
 // 0..7 and 16..23.  The pair at bit position p of both halves becomes 1024 + code * 2^p after
 // or-ing into fp16 1024.0 (exponent 25, ulp 1), and fma(v, 2^-p, -(2^(10-p) + zero)) is the
 // exact integer code - zero.
+// (w & mask) | magic in one VALU instruction.  The compiler emits an and and an or here because
+// the instruction cannot carry two literals: the mask travels in an SGPR, 0x64006400 in a VGPR.
+__device__ __forceinline__ h2 mask_or_magic(uint32_t w, uint32_t mask, uint32_t magic)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(magic));
+    return as_h2(r);
+}
+
 template <int BITS>
 __device__ __forceinline__ h8 dequant_step(uint32_t w, h2 s2, h2 z2)
 {
@@ -46,10 +55,10 @@ __device__ __forceinline__ h8 dequant_step(uint32_t w, h2 s2, h2 z2)
     h2 v0, v1, v2, v3;
     if (BITS == 4) {
         const uint32_t w1 = w >> 8;
-        h2 r0 = as_h2((w & 0x000F000Fu) | magic);
-        h2 r1 = as_h2((w & 0x00F000F0u) | magic);
-        h2 r2 = as_h2((w1 & 0x000F000Fu) | magic);
-        h2 r3 = as_h2((w1 & 0x00F000F0u) | magic);
+        h2 r0 = mask_or_magic(w, 0x000F000Fu, magic);
+        h2 r1 = mask_or_magic(w, 0x00F000F0u, magic);
+        h2 r2 = mask_or_magic(w1, 0x000F000Fu, magic);
+        h2 r3 = mask_or_magic(w1, 0x00F000F0u, magic);
         const h2 c0 = (h2){(_Float16)-1024.f, (_Float16)-1024.f} - z2;
         const h2 c1 = (h2){(_Float16)-64.f, (_Float16)-64.f} - z2;
         const h2 i16 = (h2){(_Float16)0.0625f, (_Float16)0.0625f};
@@ -58,10 +67,10 @@ __device__ __forceinline__ h8 dequant_step(uint32_t w, h2 s2, h2 z2)
         v2 = (r2 + c0) * s2;
         v3 = __builtin_elementwise_fma(r3, i16, c1) * s2;
     } else {
-        h2 r0 = as_h2((w & 0x00030003u) | magic);
-        h2 r1 = as_h2((w & 0x000C000Cu) | magic);
-        h2 r2 = as_h2((w & 0x00300030u) | magic);
-        h2 r3 = as_h2((w & 0x00C000C0u) | magic);
+        h2 r0 = mask_or_magic(w, 0x00030003u, magic);
+        h2 r1 = mask_or_magic(w, 0x000C000Cu, magic);
+        h2 r2 = mask_or_magic(w, 0x00300030u, magic);
+        h2 r3 = mask_or_magic(w, 0x00C000C0u, magic);
         const h2 c0 = (h2){(_Float16)-1024.f, (_Float16)-1024.f} - z2;
         const h2 c1 = (h2){(_Float16)-256.f, (_Float16)-256.f} - z2;
         const h2 c2 = (h2){(_Float16)-64.f, (_Float16)-64.f} - z2;
