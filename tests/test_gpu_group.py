@@ -78,3 +78,22 @@ def test_group_argument_errors(dz):
         # T == 0 is a no-op
         assert dz.dz_linear_group(c.h, cs.dx, [cs.dW], [cs.packed], cs.dids, [o], 0, [32], 256, 4, 64) == dz.DZ_OK
         assert dz.dz_check(c.h) == dz.DZ_OK
+
+
+def test_group_at_the_pointer_limit(dz):
+    """Three projections x DZ_MAX_DELTAS deltas = the most packed-delta pointers one launch carries."""
+    import oracle
+    with dz.Context(0) as c:
+        T, K, D = 24, 256, dz.DZ_MAX_DELTAS
+        g = ("limit", T, K, D, 4, 128, "uniform", [16, 32, 16])
+        cases = _make(dz, c, g)
+        outs = [cs.out(fill=7.0) for cs in cases]
+        dz.dz_linear_group(c.h, cases[0].dx, [cs.dW for cs in cases], [cs.packed for cs in cases], cases[0].dids,
+                           outs, T, g[7], K, 4, 128)
+        assert dz.dz_check(c.h) == dz.DZ_OK
+        for p, cs in enumerate(cases):
+            assert_close(outs[p], _oracle(cs, cases[0].x, cases[0].ids), f"limit projection {p}")
+        # one projection more would not fit
+        P = 4
+        assert dz.dz_linear_group(c.h, cases[0].dx, [cases[0].dW] * P, [cases[0].packed] * P, cases[0].dids,
+                                  [outs[0]] * P, T, [16] * P, K, 4, 128, check=False) == dz.DZ_ERR_ARG

@@ -127,3 +127,21 @@ def test_degenerate_calls(dz):
         assert dz.dz_linear(c.h, cs.dx, cs.dW, cs.packed * 65, cs.dids, o, cs.T, cs.N, cs.K, 4, 64, check=False) == dz.DZ_ERR_ARG
         assert dz.dz_base_gemm(c.h, cs.dx.view(-1)[1:], cs.dW, o, 1, cs.N, cs.K, check=False) == dz.DZ_ERR_ALIGN
         assert dz.dz_check(c.h) == dz.DZ_OK
+
+
+def test_maximum_tables(dz):
+    """The sizes that fill the kernels' tables: DZ_MAX_DELTAS resident deltas, 64 requests that all
+    name different deltas (64 one-row segments), and a batch where every request names the same one."""
+    with dz.Context(0) as c:
+        T, N, K, D = 64, 32, 256, dz.DZ_MAX_DELTAS
+        ids = (np.arange(T, dtype=np.int32) * 2 + 1)[::-1].copy()        # 64 distinct deltas, descending order
+        cs = Case(dz, c.h, 11, T, N, K, D, 2, 64, ids)
+        _run_all(dz, c, cs, "64 segments of 128 deltas")
+        cs.ids = torch.full((T,), D - 1, dtype=torch.int32)
+        cs.dids = cs.ids.cuda()
+        import oracle
+        ref = oracle.c.linear(cs.x.numpy(), cs.W.numpy(), cs.dense, cs.ids.numpy())
+        o = cs.out(fill=7.0)
+        dz.dz_linear(c.h, cs.dx, cs.dW, cs.packed, cs.dids, o, T, N, K, 2, 64)
+        assert_close(o, ref, "one segment of 64 rows, last delta")
+        assert dz.dz_check(c.h) == dz.DZ_OK
