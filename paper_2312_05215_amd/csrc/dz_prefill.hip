@@ -13,8 +13,10 @@
 //     (double buffered; the next slice is fetched in four batches that ride along with the four
 //     base steps, each batch loaded one step before it is stored) and every B fragment read from
 //     LDS feeds 4 dense or 2 sparse MFMAs;
-//   * the order of loads and MFMAs is written out and pinned with scheduling fences: W three
-//     steps ahead, B fragments two column blocks ahead, the next packed tile one delta ahead;
+//   * the order of loads and MFMAs is written out and pinned with scheduling fences: W one step
+//     ahead (three without deltas), B fragments two column blocks ahead, the next packed tile
+//     one delta ahead; a fused launch multiplies its delta tiles between the base steps of the
+//     k tile, so the loads of the next steps are in flight during the delta work;
 //   * deltas: contiguous segments of the sorted order; a segment multiplies only the column blocks
 //     it overlaps, and in a block shared with a neighbour the lanes of foreign request rows read a
 //     zero row of LDS, so the sparse MFMAs accumulate into the same registers as the base product;
@@ -255,7 +257,15 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     ci.kt = 0; ci.seg = 0;
     const int ndelta = nseg * g.KT;  // delta tiles this workgroup multiplies
     int ti = 0;
-    constexpr int DIST = 3;          // W prefetch distance in steps
+#ifndef PF_ILV
+#define PF_ILV 1
+#endif
+    // Fused launches multiply the delta tiles between the base steps of their k tile -- segment sg
+    // after step sg % 4 -- so that the W and x loads each step sends out keep flowing during the
+    // delta work; the W ring is then two buffers deep (one step ahead), which leaves the registers
+    // for it.  Base-only launches prefetch W three steps ahead.
+    constexpr bool ILV = HAS_BASE && HAS_DELTA && PF_ILV;
+    constexpr int DIST = ILV ? 1 : 3;          // W prefetch distance in steps
     if constexpr (HAS_BASE) {
         base_issue<PR>(rw, wrow, lo.w, 0, bwA);
         if constexpr (DIST == 3) {
@@ -263,12 +273,21 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
             base_issue<PR>(rw, wrow, lo.w, 2, bwC);
         }
     }
+    int cs = 0;                      // interleaved order: the step the fetch cursor is at
 #define PF_DISSUE(buf)                                                                                             \
     do {                                                                                                           \
         delta_issue<BITS, GROUP, PR>(ci, ti < ndelta, g, rtc, lo, s_dptr, s_seg_delta, (uint32_t)off_idx,          \
                                      (uint32_t)off_scale, blob_bytes, buf);                                        \
         ++ti;                                                                                                      \
-        if (++ci.seg >= nseg) { ci.seg = 0; ++ci.kt; }                                                             \
+        if constexpr (ILV) {                                                                                       \
+            ci.seg += 4;                                                                                           \
+            while (nseg > 0 && ci.seg >= nseg) {                                                                   \
+                if (++cs == 4) { cs = 0; ++ci.kt; }                                                                \
+                ci.seg = cs;                                                                                       \
+            }                                                                                                      \
+        } else {                                                                                                   \
+            if (++ci.seg >= nseg) { ci.seg = 0; ++ci.kt; }                                                         \
+        }                                                                                                          \
     } while (0)
     if constexpr (HAS_DELTA) PF_DISSUE(st0);
     __syncthreads();
@@ -308,6 +327,9 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
         __builtin_amdgcn_sched_barrier(0);                                                                         \
         PF_XSTORE(xcurv, xnxt, st_);                                                                               \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
+        if constexpr (ILV) {                                                                                       \
+            for (int sg = (st_); sg < nseg; sg += 4) PF_DSEG(st0, sg);                                             \
+        }                                                                                                          \
     } while (0)
         if constexpr (DIST == 3) {
             PF_BSTEP(0, bwA, bwD, xvA, xvB);
@@ -323,7 +345,9 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
 #undef PF_BSTEP
         // ---- deltas of this k tile, one packed tile per segment
         if constexpr (HAS_DELTA) {
-            for (int sg = 0; sg < nseg; ++sg) PF_DSEG(st0, sg);
+            if constexpr (!ILV) {
+                for (int sg = 0; sg < nseg; ++sg) PF_DSEG(st0, sg);
+            }
         }
 #undef PF_DSEG
         lds_barrier();                           // next slice complete, current slice no longer read
