@@ -5,7 +5,8 @@ Workload (`7b_decode`): a Llama-7B-shaped stack of linear projections per transf
 q,k,v,o 4096x4096, gate,up 11008x4096, down 4096x11008, fp16 base ~N(0,0.02) -- with 8 resident
 deltas (4-bit codes, 2:4 sparse, group 128) and a decode batch of 32 request rows whose delta ids
 are uniform over the 8 deltas.  One *step* is one pass over all linear projections of all 32
-layers (224 fused dz_linear calls: request reordering, base product, SBMM, merge), every layer
+layers -- request reordering, base product, SBMM and merge for all 224 projections, issued as 128
+calls (q,k,v share one dz_linear_group call, gate,up another; --no-group issues 224) --, every layer
 with its own weights and deltas resident in HBM (about 34 GB, far beyond the 256 MB last-level
 cache).  Attention, norms, embeddings and sampling are not part of the path.  Inputs are seeded
 and synthetic; no file is read.

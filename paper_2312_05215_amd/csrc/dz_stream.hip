@@ -16,9 +16,8 @@
 //     nobody asked for are never touched) the packed tile is loaded, codes are turned into fp16
 //     pairs with a mask-or into the mantissa of 1024.0 and one packed fma, scaled, and fed with
 //     the stored 2-bit positions to V_SMFMAC_F32_16X16X64_F16, the 2:4 sparse MFMA -- the sparse
-//     expansion costs no instruction.  A segment only multiplies the column blocks it overlaps;
-//     columns of a shared block that belong to a neighbouring segment are masked when the
-//     segment's accumulator is merged;
+//     expansion costs no instruction.  Lanes whose request row is not in the segment read an
+//     all-zero LDS row, so the delta product accumulates straight into the base accumulators;
 //   * split-k partial sums meet in fp32: every workgroup stores its partial tile, the last one to
 //     arrive for a row block (an arrival counter) adds them in fixed order and rounds to fp16
 //     once.  With one slice the result is rounded and stored directly;
