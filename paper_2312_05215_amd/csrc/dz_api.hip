@@ -137,6 +137,10 @@ int dz_create(dz_ctx **out, int device)
     ctx->no_prefill = env_int("DZ_NO_PREFILL", 0);
     DeviceGuard guard(device);
     hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
+    if (e == hipSuccess) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess) ctx->num_cus = n;
+    }
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->err_flag, 4);
     if (e == hipSuccess) e = hipMemset(ctx->err_flag, 0, 4);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->seg_counts, (size_t)(DZ_SEG_MAX_D + 1) * 4);

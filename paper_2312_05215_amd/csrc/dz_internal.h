@@ -26,6 +26,7 @@ struct dz_ctx {
     int round_tiles;        // DZ_ROUND_TILES
     int no_prefill;         // DZ_NO_PREFILL: serve large batches with the streaming kernel (chunks of 64 rows)
     int wg_waves, wg_rtiles; // DZ_WAVES, DZ_RTILES: workgroup shape of the streaming kernel
+    int num_cus;            // compute units of the device
 };
 
 #define DZ_SEG_MAX_D 8192
@@ -60,7 +61,7 @@ struct DzStreamArgs {
     int32_t *counters;
     int T, N, K, D, bits, group;   // streaming kernel: N = sum over the projections of the launch
     int accumulate;
-    int S;                      // workgroups per chunk of 64 request rows
+    int S;                      // streaming kernel: workgroups per chunk of 64 request rows; tiled kernel: k slices per tile
     int max_slots;              // most workgroups sharing one row block (partial-sum slots)
     int has_base, has_delta;
 };

@@ -6,7 +6,8 @@
 // the compute-bound phase of serving, Section 2.1), so the kernel is organised around MFMA reuse
 // instead of around HBM bytes:
 //   * a workgroup (8 waves) owns an output tile of 256 rows of N x 128 request rows (in
-//     delta-sorted order, from the segment pass) and the whole k range -- no split k;
+//     delta-sorted order, from the segment pass) and the whole k range, or half of it when the
+//     tile count fills the CUs badly (the two halves then meet in fp32);
 //   * a wave owns 2 row tiles x 8 column blocks = 16 accumulator tiles (64 registers); W and
 //     packed-delta fragments go from global memory straight into MFMA A operands (each wave owns
 //     its rows, so A needs no sharing), the 128 x 256 slice of x of the current k tile sits in LDS
@@ -25,6 +26,9 @@
 // Measured on the 13B shapes the kernel is bound by the rate at which L2 feeds the CUs (the tile
 // moves 192 KB per 256 k), not by the MFMA pipes.
 #include "dz_mma.h"
+
+int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st);
+int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
 
 namespace {
 
@@ -128,6 +132,7 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     __shared__ int s_seg_begin[PCH + 1];
     __shared__ int s_cnt[4];                // segment starts / rows with a delta seen by waves 0 and 1
     __shared__ int s_nseg;
+    __shared__ int s_last;                  // this workgroup is the last k slice of its tile to arrive
 
     const int tid = threadIdx.x;
     Geo g;
@@ -142,12 +147,18 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     lo.s = (uint32_t)g.row * (uint32_t)(F::GPT * 4);
 
     // workgroup b runs on XCD b % 8: give each XCD a contiguous run of tiles, request tiles fastest
-    const int total = NRB * nchunks;
+    // a.S slices of k per output tile (1 unless the tile count fills the CUs badly); the slices of
+    // a tile are neighbours in the numbering, so they run on the same XCD at about the same time
+    const int S = a.S;
+    const int total = NRB * nchunks * S;
     const int per_xcd = (total + 7) / 8;
     const int logical = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
     if (logical >= total) return;
-    const int rb = logical / nchunks;
-    const int chunk = logical - rb * nchunks;
+    const int tile = logical / S;
+    const int ks = logical - tile * S;
+    const int rb = tile / nchunks;
+    const int chunk = tile - rb * nchunks;
+    const int kb = (int)((long long)ks * g.KT / S), ke = (int)((long long)(ks + 1) * g.KT / S);   // k tiles [kb, ke)
     const int p0 = chunk * PCH;
     const int cnt = min(PCH, a.T - p0);
     const int RT = a.N >> 4;
@@ -246,16 +257,16 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     if (tid < PLDW / 8) *(u32x4 *)(xs_all + zoff + tid * 8) = (u32x4){0u, 0u, 0u, 0u};
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-        PF_XLOAD(xvA, 0, b);
+        PF_XLOAD(xvA, kb, b);
         PF_XSTORE(xvA, xcur, b);
     }
-    PF_XLOAD(xvA, min(1, g.KT - 1), 0);
+    PF_XLOAD(xvA, min(kb + 1, ke - 1), 0);
 
     u32x4 bwA[PR][2], bwB[PR][2], bwC[PR][2], bwD[PR][2];
     uint32_t st0[PR][SD];
     Cursor ci;                       // next delta tile to fetch: (segment, k tile)
-    ci.kt = 0; ci.seg = 0;
-    const int ndelta = nseg * g.KT;  // delta tiles this workgroup multiplies
+    ci.kt = kb; ci.seg = 0;
+    const int ndelta = nseg * (ke - kb);  // delta tiles this workgroup multiplies
     int ti = 0;
 #ifndef PF_ILV
 #define PF_ILV 1
@@ -267,10 +278,10 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     constexpr bool ILV = HAS_BASE && HAS_DELTA && PF_ILV;
     constexpr int DIST = ILV ? 1 : 3;          // W prefetch distance in steps
     if constexpr (HAS_BASE) {
-        base_issue<PR>(rw, wrow, lo.w, 0, bwA);
+        base_issue<PR>(rw, wrow, lo.w, 4 * kb, bwA);
         if constexpr (DIST == 3) {
-            base_issue<PR>(rw, wrow, lo.w, 1, bwB);
-            base_issue<PR>(rw, wrow, lo.w, 2, bwC);
+            base_issue<PR>(rw, wrow, lo.w, 4 * kb + 1, bwB);
+            base_issue<PR>(rw, wrow, lo.w, 4 * kb + 2, bwC);
         }
     }
     int cs = 0;                      // interleaved order: the step the fetch cursor is at
@@ -292,10 +303,10 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     if constexpr (HAS_DELTA) PF_DISSUE(st0);
     __syncthreads();
 
-    const int last_step = 4 * g.KT - 1;
-    for (int kt = 0; kt < g.KT; ++kt) {
+    const int last_step = 4 * ke - 1;
+    for (int kt = kb; kt < ke; ++kt) {
         // x slices fetched past the last k tile repeat it and land in the idle buffer
-        const int ktn = min(kt + 1, g.KT - 1), ktnn = min(kt + 2, g.KT - 1);
+        const int ktn = min(kt + 1, ke - 1), ktnn = min(kt + 2, ke - 1);
         // ---- base: four steps of 64 k; each step also moves a quarter of the next x slice
         h16 bq[2];
         if constexpr (HAS_BASE) {
@@ -357,6 +368,49 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
 #undef PF_XSTORE
 #undef PF_DISSUE
 
+    // ---- k slices of one tile meet in fp32: every slice stores its accumulators (agent-scope
+    // stores, register by register so that a store instruction writes 8 KB in a row), waits for
+    // them, and bumps the tile's arrival counter; the last one adds the slices in slice order --
+    // its own from registers -- so the sum does not depend on who arrives last.
+    if (S > 1) {
+        constexpr int AGENT = 0x10;
+        const uint32_t tile_bytes = (uint32_t)(PR * PJ) * THREADS * 16u;
+        const __amdgpu_buffer_rsrc_t prs = make_rsrc(a.partial, (uint32_t)(NRB * nchunks * S) * tile_bytes);
+        const uint32_t lane_off = (uint32_t)tid * 16u;
+#pragma unroll
+        for (int r = 0; r < PR; ++r)
+#pragma unroll
+            for (int j = 0; j < PJ; ++j)
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[r][j]), prs,
+                                                       lane_off + (uint32_t)(r * PJ + j) * THREADS * 16u,
+                                                       (uint32_t)(tile * S + ks) * tile_bytes, AGENT);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (tid == 0) {
+            int32_t *ctr = a.counters + tile;
+            const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int last = (old == S - 1);
+            if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+            s_last = last;
+        }
+        __syncthreads();
+        if (!s_last) return;
+#pragma unroll
+        for (int r = 0; r < PR; ++r)
+#pragma unroll
+            for (int j = 0; j < PJ; ++j) {
+                f4 sum = (f4){0.f, 0.f, 0.f, 0.f};
+                for (int sl = 0; sl < S; ++sl) {
+                    f4 v = acc[r][j];
+                    if (sl != ks)
+                        v = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                       prs, lane_off + (uint32_t)(r * PJ + j) * THREADS * 16u,
+                                                       (uint32_t)(tile * S + sl) * tile_bytes, AGENT));
+                    sum += v;
+                }
+                acc[r][j] = sum;
+            }
+    }
     // ---- results: lane 16q + c holds rows 4q..4q+3 of each row tile for request column c
     _Float16 *out = (_Float16 *)a.out;
 #pragma unroll
@@ -381,7 +435,7 @@ hipError_t launch_pf(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int total = NRB * nchunks;
+    const int total = NRB * nchunks * a.S;
     const int grid = ((total + 7) / 8) * 8;
     hipLaunchKernelGGL(k, dim3(grid), dim3(PW * 64), lds, st, a, dp, NRB, nchunks, L.off_idx, L.off_scale, L.total);
     return hipGetLastError();
@@ -397,10 +451,34 @@ hipError_t launch_pf_fmt(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, 
 }
 
 template <int PW, int PR, int PJ>
-hipError_t launch_pf_kind(const DzStreamArgs &a, const DzDeltaPtrs &dp, const DzLayout &L, hipStream_t st)
+hipError_t launch_pf_kind(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &dp, const DzLayout &L, hipStream_t st,
+                          int *rc)
 {
+    DzStreamArgs a = args;
     const int nchunks = (a.T + 16 * PJ - 1) / (16 * PJ);
     const int NRB = (a.N / 16 + PW * PR - 1) / (PW * PR);
+    // One workgroup per CU: `tiles` tiles take ceil(tiles / CUs) rounds.  Cutting k in two halves
+    // the round length and is taken when it saves at least a sixth of the rounds (320 tiles on
+    // 256 CUs: 2 rounds -> 3 half rounds); the price is an fp32 copy of the output written twice
+    // and read once, which the short tiles of a base-only launch do not earn back (measured:
+    // 5120x5120, 2048 rows: fused 308 -> 290 us, base only 188 -> 194 us).
+    const int tiles = NRB * nchunks, cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
+    a.S = 1;
+    if (ctx->force_splits > 0) a.S = ctx->force_splits;
+    else if (a.has_delta) {
+        const double r1 = (double)((tiles + cus - 1) / cus), r2 = (double)((2 * tiles + cus - 1) / cus) / 2.0;
+        if (r2 <= r1 * (5.0 / 6.0) + 1e-9) a.S = 2;
+    }
+    if (a.S > a.K / 256) a.S = a.K / 256;
+    const size_t tile_bytes = (size_t)PR * PJ * PW * 64 * 16;
+    if ((size_t)tiles * a.S * tile_bytes >= ((size_t)1 << 32)) a.S = 1;                 // 32-bit byte offsets
+    if (a.S > 1) {
+        *rc = dz_ensure_partial(ctx, (size_t)tiles * a.S * tile_bytes, st);
+        if (*rc == DZ_OK) *rc = dz_ensure_counters(ctx, tiles, st);
+        if (*rc != DZ_OK) return hipSuccess;
+    }
+    a.partial = ctx->partial;
+    a.counters = ctx->counters;
     if (a.has_base && a.has_delta) return launch_pf_fmt<PW, PR, PJ, true, true>(a, dp, NRB, nchunks, L, st);
     if (a.has_base) return launch_pf_fmt<PW, PR, PJ, true, false>(a, dp, NRB, nchunks, L, st);
     return launch_pf_fmt<PW, PR, PJ, false, true>(a, dp, NRB, nchunks, L, st);
@@ -415,8 +493,10 @@ int dz_launch_prefill(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &
     if ((unsigned long long)a.T * a.K * 2ull >= (1ull << 31)) return DZ_ERR_SHAPE;     // x offsets, bit 31 = no row
     DzLayout L = dz_make_layout(a.N, a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
     hipError_t e;
+    int rc = DZ_OK;
     // 8 waves x 2 row tiles measured faster than 4 x 4 (two waves per SIMD hide each other's waits)
-    if (ctx->wg_waves == 4) e = launch_pf_kind<4, 4, 8>(a, dp, L, st);
-    else e = launch_pf_kind<8, 2, 8>(a, dp, L, st);
+    if (ctx->wg_waves == 4) e = launch_pf_kind<4, 4, 8>(ctx, a, dp, L, st, &rc);
+    else e = launch_pf_kind<8, 2, 8>(ctx, a, dp, L, st, &rc);
+    if (rc != DZ_OK) return rc;
     return dz_set_hip_error(ctx, e);
 }
