@@ -6,8 +6,8 @@
 // the compute-bound phase of serving, Section 2.1), so the kernel is organised around MFMA reuse
 // instead of around HBM bytes:
 //   * a workgroup (8 waves) owns an output tile of 256 rows of N x 128 request rows (in
-//     delta-sorted order, from the segment pass) and the whole k range, or half of it when the
-//     tile count fills the CUs badly (the two halves then meet in fp32);
+//     delta-sorted order, from the segment pass) and the whole k range; the tiles of the last,
+//     partly filled round of one-tile-per-CU are cut into slices of k that meet in fp32;
 //   * a wave owns 2 row tiles x 8 column blocks = 16 accumulator tiles (64 registers); W and
 //     packed-delta fragments go from global memory straight into MFMA A operands (each wave owns
 //     its rows, so A needs no sharing), the 128 x 256 slice of x of the current k tile sits in LDS
@@ -146,16 +146,26 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     lo.i = (uint32_t)g.lane * 8u;
     lo.s = (uint32_t)g.row * (uint32_t)(F::GPT * 4);
 
-    // workgroup b runs on XCD b % 8: give each XCD a contiguous run of tiles, request tiles fastest
-    // a.S slices of k per output tile (1 unless the tile count fills the CUs badly); the slices of
-    // a tile are neighbours in the numbering, so they run on the same XCD at about the same time
-    const int S = a.S;
-    const int total = NRB * nchunks * S;
-    const int per_xcd = (total + 7) / 8;
-    const int logical = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
-    if (logical >= total) return;
-    const int tile = logical / S;
-    const int ks = logical - tile * S;
+    // Workgroup b runs on XCD b % 8, and workgroups start in the order of b.  Each XCD first gets a
+    // contiguous run of I0 whole tiles (request tiles fastest, so the tiles of a row block share the
+    // XCD's L2 copy of the W rows) -- together the full rounds of one tile per CU -- and then its
+    // share of the remaining tiles cut into S slices of k each, so that the last, partly filled
+    // round is short; the slices of a tile are neighbours and meet in fp32 at the end.
+    const int I0 = a.max_slots, tiles = NRB * nchunks;
+    const int Tt = (tiles - 8 * I0 + 7) / 8;            // sliced tiles per XCD
+    const int xcd = (int)(blockIdx.x % 8), bi = (int)(blockIdx.x / 8);
+    int tile, ks = 0, S = 1;
+    if (bi < I0) {
+        tile = xcd * I0 + bi;
+        if (tile >= tiles) return;
+    } else {
+        S = a.S;
+        const int tt = (bi - I0) / S;
+        ks = (bi - I0) - tt * S;
+        tile = 8 * I0 + xcd * Tt + tt;
+        if (tt >= Tt || tile >= tiles) return;
+    }
+    const int slot0 = (tile - 8 * I0) * S;              // first partial-sum slot of a sliced tile
     const int rb = tile / nchunks;
     const int chunk = tile - rb * nchunks;
     const int kb = (int)((long long)ks * g.KT / S), ke = (int)((long long)(ks + 1) * g.KT / S);   // k tiles [kb, ke)
@@ -375,7 +385,7 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     if (S > 1) {
         constexpr int AGENT = 0x10;
         const uint32_t tile_bytes = (uint32_t)(PR * PJ) * THREADS * 16u;
-        const __amdgpu_buffer_rsrc_t prs = make_rsrc(a.partial, (uint32_t)(NRB * nchunks * S) * tile_bytes);
+        const __amdgpu_buffer_rsrc_t prs = make_rsrc(a.partial, (uint32_t)(8 * Tt * S) * tile_bytes);
         const uint32_t lane_off = (uint32_t)tid * 16u;
 #pragma unroll
         for (int r = 0; r < PR; ++r)
@@ -383,11 +393,11 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
             for (int j = 0; j < PJ; ++j)
                 __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[r][j]), prs,
                                                        lane_off + (uint32_t)(r * PJ + j) * THREADS * 16u,
-                                                       (uint32_t)(tile * S + ks) * tile_bytes, AGENT);
+                                                       (uint32_t)(slot0 + ks) * tile_bytes, AGENT);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (tid == 0) {
-            int32_t *ctr = a.counters + tile;
+            int32_t *ctr = a.counters + (tile - 8 * I0);
             const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const int last = (old == S - 1);
             if (last) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
@@ -405,7 +415,7 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
                     if (sl != ks)
                         v = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(
                                                        prs, lane_off + (uint32_t)(r * PJ + j) * THREADS * 16u,
-                                                       (uint32_t)(tile * S + sl) * tile_bytes, AGENT));
+                                                       (uint32_t)(slot0 + sl) * tile_bytes, AGENT));
                     sum += v;
                 }
                 acc[r][j] = sum;
@@ -435,8 +445,8 @@ hipError_t launch_pf(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int total = NRB * nchunks * a.S;
-    const int grid = ((total + 7) / 8) * 8;
+    const int tail = NRB * nchunks - 8 * a.max_slots;
+    const int grid = 8 * (a.max_slots + ((tail + 7) / 8) * a.S);
     hipLaunchKernelGGL(k, dim3(grid), dim3(PW * 64), lds, st, a, dp, NRB, nchunks, L.off_idx, L.off_scale, L.total);
     return hipGetLastError();
 }
@@ -457,24 +467,32 @@ hipError_t launch_pf_kind(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPt
     DzStreamArgs a = args;
     const int nchunks = (a.T + 16 * PJ - 1) / (16 * PJ);
     const int NRB = (a.N / 16 + PW * PR - 1) / (PW * PR);
-    // One workgroup per CU: `tiles` tiles take ceil(tiles / CUs) rounds.  Cutting k in two halves
-    // the round length and is taken when it saves at least a sixth of the rounds (320 tiles on
-    // 256 CUs: 2 rounds -> 3 half rounds); the price is an fp32 copy of the output written twice
-    // and read once, which the short tiles of a base-only launch do not earn back (measured:
-    // 5120x5120, 2048 rows: fused 308 -> 290 us, base only 188 -> 194 us).
-    const int tiles = NRB * nchunks, cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
+    // One workgroup per CU: `tiles` tiles take ceil(tiles / CUs) rounds, the last one partly
+    // filled.  The tiles of the full rounds run whole; those of the last round are cut into up to
+    // four slices of k, as many as still fit the CUs at once (320 tiles on 256 CUs: 256 whole,
+    // then 64 x 4 quarter tiles), and only they pay for the fp32 meeting.
+    const int tiles = NRB * nchunks;
+    int cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
+    cus -= cus % 8;
     a.S = 1;
-    if (ctx->force_splits > 0) a.S = ctx->force_splits;
-    else if (a.has_delta) {
-        const double r1 = (double)((tiles + cus - 1) / cus), r2 = (double)((2 * tiles + cus - 1) / cus) / 2.0;
-        if (r2 <= r1 * (5.0 / 6.0) + 1e-9) a.S = 2;
+    a.max_slots = (tiles + 7) / 8;          // whole tiles per XCD: all of them
+    if (ctx->force_splits > 0) {
+        a.S = ctx->force_splits;
+        a.max_slots = 0;
+    } else if (cus >= 8 && tiles % cus != 0) {
+        const int whole = (tiles / cus) * cus, tail = tiles - whole;
+        int S = cus / tail;
+        if (S > 4) S = 4;
+        if (S > 1) { a.S = S; a.max_slots = whole / 8; }
     }
     if (a.S > a.K / 256) a.S = a.K / 256;
     const size_t tile_bytes = (size_t)PR * PJ * PW * 64 * 16;
-    if ((size_t)tiles * a.S * tile_bytes >= ((size_t)1 << 32)) a.S = 1;                 // 32-bit byte offsets
+    const int sliced = 8 * ((tiles - 8 * a.max_slots + 7) / 8);
+    if (a.S > 1 && (size_t)sliced * a.S * tile_bytes >= ((size_t)1 << 32)) a.S = 1;     // 32-bit byte offsets
+    if (a.S <= 1) { a.S = 1; a.max_slots = (tiles + 7) / 8; }
     if (a.S > 1) {
-        *rc = dz_ensure_partial(ctx, (size_t)tiles * a.S * tile_bytes, st);
-        if (*rc == DZ_OK) *rc = dz_ensure_counters(ctx, tiles, st);
+        *rc = dz_ensure_partial(ctx, (size_t)sliced * a.S * tile_bytes, st);
+        if (*rc == DZ_OK) *rc = dz_ensure_counters(ctx, sliced, st);
         if (*rc != DZ_OK) return hipSuccess;
     }
     a.partial = ctx->partial;
