@@ -57,6 +57,50 @@ __device__ __forceinline__ void base_step(const u32x4 (&buf)[R][2], const _Float
     }
 }
 
+// One step of a tile whose request rows all belong to one delta: the B fragment a column block
+// reads for the base product also feeds the sparse MFMA of the delta (av: the step's dequantised
+// kept values, idxw: their positions, ODD: which half of idxw the step uses).
+template <int R, int J, bool NEXT, int ODD>
+__device__ __forceinline__ void fused_step(const u32x4 (&buf)[R][2], const h8 (&av)[R], const uint32_t (&idxw)[R],
+                                           const _Float16 *xs, const Geo &g, const int (&brow)[J], int kofs,
+                                           f4 (&acc)[R][J], h16 (&bq)[2])
+{
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const h16 b = bq[j & 1];
+        if (j + 2 < J) bq[j & 1] = load_b(xs, brow[j + 2], g, kofs);
+        else if (NEXT) bq[j & 1] = load_b(xs, brow[j + 2 - J], g, kofs + 64);
+        const h8 b0 = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, 6, 7);
+        const h8 b1 = __builtin_shufflevector(b, b, 8, 9, 10, 11, 12, 13, 14, 15);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, buf[r][0]), b0, acc[r][j], 0, 0, 0);
+            acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, buf[r][1]), b1, acc[r][j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[r][j] = smfmac<ODD>(av[r], b, acc[r][j], (int)idxw[r]);
+        __builtin_amdgcn_sched_barrier(0);      // keep the reads two blocks ahead of their MFMAs
+    }
+}
+
+// Dequantised kept values and positions of step s of a packed tile held in stage registers.
+template <int BITS, int GROUP, int R>
+__device__ __forceinline__ void step_dequant(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], int s, h8 (&av)[R],
+                                             uint32_t (&idxw)[R])
+{
+    typedef Fmt<BITS, GROUP> F;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const h2 sz2 = as_h2(st[r][F::SC0 + s * F::GPT / 4]);
+        const h2 s2 = (h2){sz2.x, sz2.x};
+        const h2 z2 = (h2){sz2.y, sz2.y};
+        uint32_t w;
+        if (BITS == 4) { w = st[r][s]; idxw[r] = st[r][4 + (s >> 1)]; }
+        else { w = st[r][s >> 1] >> (8 * (s & 1)); idxw[r] = st[r][2 + (s >> 1)]; }
+        av[r] = dequant_step<BITS>(w, s2, z2);
+    }
+}
+
 // Packed tile (16 rows x 256 k) of R row tiles -> MFMA A operands of the four steps.
 template <int BITS, int GROUP, int R>
 __device__ __forceinline__ void delta_dequant(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], h8 (&av)[4][R],
@@ -314,7 +358,47 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     __syncthreads();
 
     const int last_step = 4 * ke - 1;
-    for (int kt = kb; kt < ke; ++kt) {
+    // A tile whose request rows all name the same delta (long prompts: most tiles) runs the delta
+    // product inside the base steps: one read of a B fragment from LDS feeds both.
+    bool whole = false;
+    if constexpr (ILV) whole = nseg == 1 && s_seg_begin[0] == 0 && s_seg_begin[1] >= cnt;
+    whole = __builtin_amdgcn_readfirstlane(whole);
+    if constexpr (ILV) {
+        if (whole) {
+            for (int kt = kb; kt < ke; ++kt) {
+                const int ktn = min(kt + 1, ke - 1), ktnn = min(kt + 2, ke - 1);
+                h16 bq[2];
+                bq[0] = load_b(xcur, brow[0], g, 0);
+                bq[1] = load_b(xcur, brow[1], g, 0);
+#define PF_FSTEP(st_, cur, nxt, xcurv, xnxtv)                                                                      \
+    do {                                                                                                           \
+        PF_XLOAD(xnxtv, (st_) < 3 ? ktn : ktnn, ((st_) + 1) & 3);                                                  \
+        base_issue<PR>(rw, wrow, lo.w, min(kt * 4 + (st_) + DIST, last_step), nxt);                                \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        h8 av[PR];                                                                                                 \
+        uint32_t idxw[PR];                                                                                         \
+        step_dequant<BITS, GROUP, PR>(st0, st_, av, idxw);                                                         \
+        if ((st_) == 3) {       /* the stage registers are free: request the next k tile's packed tile */          \
+            __builtin_amdgcn_sched_barrier(0);                                                                     \
+            PF_DISSUE(st0);                                                                                        \
+        }                                                                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        fused_step<PR, PJ, ((st_) < 3), ((st_) & 1)>(cur, av, idxw, xcur, g, brow, (st_) * 64, acc, bq);           \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        PF_XSTORE(xcurv, xnxt, st_);                                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+    } while (0)
+                PF_FSTEP(0, bwA, bwB, xvA, xvB);
+                PF_FSTEP(1, bwB, bwA, xvB, xvA);
+                PF_FSTEP(2, bwA, bwB, xvA, xvB);
+                PF_FSTEP(3, bwB, bwA, xvB, xvA);
+#undef PF_FSTEP
+                lds_barrier();
+                _Float16 *t = xcur; xcur = xnxt; xnxt = t;
+            }
+        }
+    }
+    for (int kt = kb; kt < (whole ? kb : ke); ++kt) {
         // x slices fetched past the last k tile repeat it and land in the idle buffer
         const int ktn = min(kt + 1, ke - 1), ktnn = min(kt + 2, ke - 1);
         // ---- base: four steps of 64 k; each step also moves a quarter of the next x slice

@@ -145,3 +145,22 @@ def test_maximum_tables(dz):
         dz.dz_linear(c.h, cs.dx, cs.dW, cs.packed, cs.dids, o, T, N, K, 2, 64)
         assert_close(o, ref, "one segment of 64 rows, last delta")
         assert dz.dz_check(c.h) == dz.DZ_OK
+
+
+def test_tiles_of_one_delta(dz):
+    """Large batches whose 128-row tiles each belong to one delta (the fused path of the tiled
+    kernel), next to tiles that mix deltas and base-only requests (the general path)."""
+    with dz.Context(0) as c:
+        T, N, K, D = 300, 96, 768, 3
+        ids = np.concatenate([np.zeros(256, np.int32), np.full(44, 2, np.int32)])
+        for bits, G in ((4, 128), (2, 64)):
+            cs = Case(dz, c.h, 21, T, N, K, D, bits, G, ids)
+            _run_all(dz, c, cs, f"one delta per tile b{bits}")
+        # the same rows in scrambled order with base-only requests among them: after sorting, the
+        # first tile is all delta 0, the second mixes delta 0 and delta 2, the third ends in rows
+        # that name no delta
+        rng = np.random.default_rng(5)
+        ids2 = np.concatenate([np.zeros(200, np.int32), np.full(80, 2, np.int32), np.full(20, -1, np.int32)])
+        rng.shuffle(ids2)
+        cs = Case(dz, c.h, 22, T, N, K, D, 4, 128, ids2)
+        _run_all(dz, c, cs, "mixed tiles")
