@@ -21,6 +21,9 @@
 //   * deltas: contiguous segments of the sorted order; a segment multiplies only the column blocks
 //     it overlaps, and in a block shared with a neighbour the lanes of foreign request rows read a
 //     zero row of LDS, so the sparse MFMAs accumulate into the same registers as the base product;
+//   * a tile whose request rows all name one delta runs a shorter loop: each step dequantises its
+//     quarter of the packed tile and issues the sparse MFMAs of a column block right behind the
+//     dense ones, on the B fragment those already hold;
 //   * workgroups are numbered so that the request tiles of one row block run on the same XCD
 //     at the same time and share its L2 copy of the W rows.
 // Measured on the 13B shapes the kernel is bound by the rate at which L2 feeds the CUs (the tile
