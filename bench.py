@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-group", action="store_true",
                     help="one dz_linear call per projection instead of one dz_linear_group call for q,k,v and one for gate,up")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the step's launches into a HIP graph once and time its replays")
     ap.add_argument("--no-compare", action="store_true",
                     help="skip the extra timing of the other launch grouping (keeps a profile of the run to one kind of launch)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -146,7 +148,16 @@ def main():
         assert dz.dz_check(ctx.h) == dz.DZ_OK
         return ev0.elapsed_time(ev1) / steps
 
-    ms_per_step = timed(step, args.steps, args.warmup)
+    if args.graph:
+        step()                                  # eager once: sizes the library's workspace
+        assert dz.dz_check(ctx.h) == dz.DZ_OK
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        ms_per_step = timed(graph.replay, args.steps, args.warmup)
+    else:
+        ms_per_step = timed(step, args.steps, args.warmup)
     # the same work as one call per projection, for comparison (not part of `value`)
     ms_other = None if args.no_compare else timed(step_single if grouped else step_grouped, max(1, args.steps // 2), 1)
 
@@ -217,6 +228,7 @@ def main():
                    "deltas": cfg.D, "active_deltas": n_active, "bits": cfg.bits, "group": cfg.group,
                    "projections_per_layer": len(projs), "launches_per_layer": len(groups) if grouped else len(projs),
                    "grouping": "q,k,v in one call; gate,up in one call" if grouped else "one call per projection",
+                   "submission": "replays of one HIP graph of the step" if args.graph else "eager launches",
                    "gen_seconds": round(gen_s, 1)},
         ("ms_per_step_one_call_per_projection" if grouped else "ms_per_step_grouped"):
             None if ms_other is None else round(ms_other, 4),

@@ -32,6 +32,9 @@
  * Ownership and synchronisation: the caller owns every buffer it passes.  The library owns only
  * the workspace inside dz_ctx (segment tables, split-K partial sums, an error flag), which may grow
  * on a call that needs more than any earlier call (that growth synchronises the stream once).
+ * A stream that is being captured into a HIP graph can be passed once an eager call with the same
+ * shapes has sized the workspace: the calls then record only kernels.  A call that would have to
+ * grow the workspace during a capture returns DZ_ERR_HIP and records nothing.
  * Otherwise all compute entry points only enqueue work on `stream` (a hipStream_t passed as
  * void*, NULL = the default stream) and return; nothing is synchronised except in dz_check and
  * dz_destroy.  One dz_ctx serves one stream at a time.  x and out must not overlap.

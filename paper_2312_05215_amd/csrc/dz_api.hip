@@ -50,11 +50,24 @@ int dz_set_hip_error(dz_ctx *ctx, hipError_t e)
     return DZ_ERR_HIP;
 }
 
+// The workspace can only grow between launches: growing synchronises the stream and allocates,
+// neither of which a stream that is being recorded into a graph allows.  Such a call fails here,
+// before it touches the stream, so the capture itself stays valid.
+static int quiesce_for_growth(dz_ctx *ctx, hipStream_t st)
+{
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    hipError_t e = hipStreamIsCapturing(st, &cs);
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    if (cs != hipStreamCaptureStatusNone) return dz_set_hip_error(ctx, hipErrorStreamCaptureUnsupported);
+    e = hipStreamSynchronize(st);                       // earlier launches may still read the old buffer
+    return dz_set_hip_error(ctx, e);
+}
+
 int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st)
 {
     if (bytes <= ctx->partial_bytes) return DZ_OK;
-    hipError_t e = hipStreamSynchronize(st);            // earlier launches may still read the old buffer
-    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    if (int rc = quiesce_for_growth(ctx, st)) return rc;
+    hipError_t e;
     if (ctx->partial) (void)hipFree(ctx->partial);
     ctx->partial = nullptr;
     ctx->partial_bytes = 0;
@@ -68,8 +81,8 @@ int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st)
 int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st)
 {
     if (n <= ctx->counters_cap) return DZ_OK;
-    hipError_t e = hipStreamSynchronize(st);
-    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    if (int rc = quiesce_for_growth(ctx, st)) return rc;
+    hipError_t e;
     if (ctx->counters) (void)hipFree(ctx->counters);
     ctx->counters = nullptr;
     ctx->counters_cap = 0;
@@ -85,8 +98,8 @@ int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st)
 static int ensure_seg(dz_ctx *ctx, int T, hipStream_t st)
 {
     if (T <= ctx->seg_cap) return DZ_OK;
-    hipError_t e = hipStreamSynchronize(st);
-    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    if (int rc = quiesce_for_growth(ctx, st)) return rc;
+    hipError_t e;
     if (ctx->seg_perm) (void)hipFree(ctx->seg_perm);
     if (ctx->seg_key) (void)hipFree(ctx->seg_key);
     ctx->seg_perm = ctx->seg_key = nullptr;
