@@ -142,8 +142,8 @@ int dz_create(dz_ctx **out, int device)
     memset(ctx, 0, sizeof(*ctx));
     ctx->device = device;
     ctx->force_splits = env_int("DZ_SPLITS", 0);
-    ctx->target_wgs = env_int("DZ_TARGET_WGS", 512);
-    if (ctx->target_wgs < 1) ctx->target_wgs = 1;
+    ctx->target_wgs = env_int("DZ_TARGET_WGS", 0);       // 0: eight waves per CU
+    if (ctx->target_wgs < 0) ctx->target_wgs = 0;
     ctx->wg_waves = env_int("DZ_WAVES", 0);
     ctx->wg_rtiles = env_int("DZ_RTILES", 0);
     ctx->round_tiles = env_int("DZ_ROUND_TILES", 0);

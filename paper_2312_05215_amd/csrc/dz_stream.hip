@@ -148,17 +148,17 @@ __device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BI
     }
 }
 
+#ifndef DZ_DSTG_SMALL
+#define DZ_DSTG_SMALL 3
+#endif
 template <int BITS, int GROUP, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((R == 1 && J <= 2) ? 4 : 2)))
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int round_tiles)
 {
     typedef Fmt<BITS, GROUP> F;
     constexpr int SD = F::SD;
     constexpr int THREADS = WAVES * 64;
     constexpr int ZROW = 16 * J;            // an all-zero LDS row for column slots without a request
-#ifndef DZ_DSTG_SMALL
-#define DZ_DSTG_SMALL 3
-#endif
     // packed-tile stage buffers of the delta phase (DSTG - 1 tiles in flight): as many as the
     // register budget of the shape's occupancy allows
     constexpr int DSTG = (R == 1 && J <= 2) ? DZ_DSTG_SMALL : 5;
@@ -629,7 +629,11 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group
     // number of workgroups per chunk: the target (a multiple of the CU count) unless the call has
     // fewer (row block, k tile) positions than that
     const long long P = (long long)NRB * KT;
-    long long G = ctx->force_splits > 0 ? (long long)ctx->force_splits * NRB : ctx->target_wgs;
+    // Eight waves per CU (two per SIMD) stream fastest: one workgroup of 8 waves or two of 4 per CU;
+    // twice as many waves measured 7-10 % slower on every decode shape
+    const int cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
+    const long long auto_wgs = (long long)cus * 8 / WAVES;
+    long long G = ctx->force_splits > 0 ? (long long)ctx->force_splits * NRB : (ctx->target_wgs > 0 ? ctx->target_wgs : auto_wgs);
     if (G > P) G = P;
     if (G < 1) G = 1;
     // most workgroups that can share one row block = partial slots needed
