@@ -148,6 +148,9 @@ __device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BI
     }
 }
 
+#ifndef DZ_RCAP_SMALL
+#define DZ_RCAP_SMALL 8
+#endif
 #ifndef DZ_DSTG_SMALL
 #define DZ_DSTG_SMALL 3
 #endif
@@ -321,7 +324,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         // two batches of loads per thread cover the largest round: the first is written to LDS
         // right away, the second stays in registers while the weight prefetch is issued behind it
         // (one batch for the whole slice would not fit the registers next to that prefetch)
-        constexpr int XB = (16 * J * ((J <= 2) ? 4 : 2) * 32 + 2 * THREADS - 1) / (2 * THREADS);
+        constexpr int XB = (16 * J * ((J <= 2) ? DZ_RCAP_SMALL : 2) * 32 + 2 * THREADS - 1) / (2 * THREADS);
         u32x4 xv[XB];
         int xdst[XB];
 #define DZ_XLOAD(i0)                                                                                               \
@@ -647,7 +650,7 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group
     if ((size_t)max_slots * Tp * a.N * 4 >= ((size_t)1 << 32)) return DZ_ERR_SHAPE;    // 32-bit byte offsets
     if ((unsigned long long)a.T * a.K * 2ull >= 0xFFFFFFF0ull) return DZ_ERR_SHAPE;
     // one batch of x loads per thread must cover a round (see XB in the kernel)
-    const int round_cap = (J <= 2 ? 4 : 2);
+    const int round_cap = (J <= 2 ? DZ_RCAP_SMALL : 2);
     int round_tiles = (ctx->round_tiles > 0 && ctx->round_tiles < round_cap) ? ctx->round_tiles : round_cap;
     const int max_slice = (int)((P + G - 1) / G) < KT ? (int)((P + G - 1) / G) : KT;
     if (round_tiles > max_slice) round_tiles = max_slice;
