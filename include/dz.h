@@ -162,6 +162,46 @@ int dz_linear_group(dz_ctx *ctx, const void *x_f16, int P, const void *const *W_
  * index outside [-1, D) (that request was served with the base model only), else DZ_OK. */
 int dz_check(dz_ctx *ctx, void *stream);
 
+/*
+ * Resident-delta cache: the step before the hot path.  The engine keeps the base model on the GPU
+ * and brings compressed deltas in on demand (Section 5.1), a fixed, pre-set number of them per
+ * batch at most, moving deltas between GPU memory, host memory and disk as needed (Section 5.4,
+ * paragraph "Scalability").  The paper names no replacement rule; this cache evicts the least
+ * recently used delta.
+ *
+ * A cache owns `slots` device buffers of slot_bytes each (16-byte aligned, allocated at creation,
+ * freed by dz_cache_destroy, which synchronises the device).  dz_cache_acquire makes the packed
+ * deltas named by keys[0..n) resident and returns their device addresses:
+ *   - a key already resident is a hit: nothing is copied;
+ *   - otherwise a slot is taken -- an empty one first (lowest index), else the least recently
+ *     handed-out slot among those neither handed out by this call nor by the previous one -- and
+ *     host_blobs[i] (HOST memory, `bytes` <= slot_bytes long, pinned if the copy is to overlap with
+ *     compute; it must stay valid until the copy has run) is copied into it asynchronously on
+ *     copy_stream.
+ * Ordering is by events, nothing is synchronised: the copies wait for the work that was enqueued
+ * on compute_stream before this call (an evicted delta may still be read by it), and
+ * compute_stream waits for the copies, so work enqueued on compute_stream after the call may read
+ * every returned address.  Because the slots of the previous call are never evicted, a caller can
+ * acquire the deltas of batch i+1 before it enqueues the compute of batch i and have the copies
+ * run under that compute.  One cache serves one compute stream.
+ * device_blobs_out[n] receives the addresses; slot_out[n] (slot index) and hit_out[n] (1 = was
+ * resident) may be NULL.  Keys may repeat within a call (the repeats are hits).  A call with
+ * n == 0 does nothing (it does not count as "the previous call" afterwards).
+ * Errors: DZ_ERR_ARG for null / negative arguments, bytes > slot_bytes, or more keys to bring in
+ * than there are slots outside this and the previous call's (nothing is changed then);
+ * DZ_ERR_HIP for runtime failures.
+ * dz_cache_create with device < 0 makes a cache without device memory that takes the same
+ * decisions and copies nothing (addresses come back NULL): for planning and for tests.
+ */
+typedef struct dz_cache dz_cache;
+int dz_cache_create(dz_cache **cache, int device, int slots, size_t slot_bytes);
+int dz_cache_destroy(dz_cache *cache);
+int dz_cache_acquire(dz_cache *cache, int n, const int64_t *keys, const void *const *host_blobs,
+                     size_t bytes, const void **device_blobs_out, int32_t *slot_out,
+                     int32_t *hit_out, void *copy_stream, void *compute_stream);
+/* Totals since creation; any pointer may be NULL. */
+int dz_cache_stats(const dz_cache *cache, int64_t *hits, int64_t *misses, int64_t *evictions);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,6 +11,7 @@ __all__ = [
     "DZ_MAX_DELTAS", "DzError", "lib", "lib_path", "dz_strerror", "dz_create", "dz_destroy",
     "dz_packed_bytes", "dz_pack_delta", "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm",
     "dz_linear", "dz_linear_group", "dz_check", "Context", "SYMBOLS", "DZ_MAX_GROUP",
+    "dz_cache_create", "dz_cache_destroy", "dz_cache_acquire", "dz_cache_stats",
 ]
 
 DZ_OK, DZ_ERR_ARG, DZ_ERR_SHAPE, DZ_ERR_BITS, DZ_ERR_ALIGN, DZ_ERR_HIP, DZ_ERR_INDEX = 0, -1, -2, -3, -4, -5, -6
@@ -18,7 +19,8 @@ DZ_MAX_DELTAS = 128
 DZ_MAX_GROUP = 4
 
 SYMBOLS = ["dz_strerror", "dz_last_hip_error", "dz_create", "dz_destroy", "dz_packed_bytes", "dz_pack_delta",
-           "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm", "dz_linear", "dz_linear_group", "dz_check"]
+           "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm", "dz_linear", "dz_linear_group", "dz_check",
+           "dz_cache_create", "dz_cache_destroy", "dz_cache_acquire", "dz_cache_stats"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _lib = None
@@ -61,6 +63,12 @@ def lib() -> ctypes.CDLL:
         L.dz_linear_group.argtypes = [vp, vp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, ctypes.POINTER(vp),
                                       ctypes.POINTER(ci), ci, ci, ci, ci, vp]
         L.dz_check.argtypes = [vp, vp]
+        i64p, i32p = ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32)
+        L.dz_cache_create.argtypes = [ctypes.POINTER(vp), ci, ci, ctypes.c_size_t]
+        L.dz_cache_destroy.argtypes = [vp]
+        L.dz_cache_acquire.argtypes = [vp, ci, i64p, ctypes.POINTER(vp), ctypes.c_size_t, ctypes.POINTER(vp), i32p, i32p,
+                                       vp, vp]
+        L.dz_cache_stats.argtypes = [vp, i64p, i64p, i64p]
         for name in SYMBOLS:
             getattr(L, name)
         _lib = L
@@ -74,6 +82,8 @@ def dz_strerror(rc: int) -> str:
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     if t is None:
         return None
+    if isinstance(t, int):          # a raw device address (e.g. from dz_cache_acquire)
+        return t
     if not t.is_cuda:
         raise ValueError("libdz takes device tensors")
     if not t.is_contiguous():
@@ -176,6 +186,54 @@ def dz_linear_group(ctx, x, W_list, packed_deltas_list, token_to_delta, out_list
 
 def dz_check(ctx, stream=None) -> int:
     return lib().dz_check(ctx, _stream(stream))
+
+
+def dz_cache_create(device: int, slots: int, slot_bytes: int) -> int:
+    """device < 0: a cache that only takes the decisions (no device memory, nothing copied)."""
+    h = ctypes.c_void_p()
+    rc = lib().dz_cache_create(ctypes.byref(h), int(device), int(slots), int(slot_bytes))
+    if rc != DZ_OK:
+        raise DzError(rc, "dz_cache_create")
+    return h.value
+
+
+def dz_cache_destroy(cache: int) -> int:
+    return lib().dz_cache_destroy(cache)
+
+
+def dz_cache_acquire(cache, keys: Sequence[int], host_blobs: Optional[Sequence[Optional[torch.Tensor]]], nbytes: int,
+                     copy_stream=None, compute_stream=None, check=True):
+    """Returns (rc, device addresses, slots, hits).  host_blobs: host tensors (pinned for overlap), one per key;
+    None for a cache created with device < 0.  Streams: torch streams or raw handles; None = the current stream."""
+    n = len(keys)
+    karr = (ctypes.c_int64 * max(n, 1))(*[int(k) for k in keys])
+    harr = (ctypes.c_void_p * max(n, 1))()
+    if host_blobs is not None:
+        if len(host_blobs) != n:
+            raise ValueError("dz_cache_acquire: one host blob per key")
+        for i, t in enumerate(host_blobs):
+            if t is not None:
+                if t.is_cuda or not t.is_contiguous():
+                    raise ValueError("dz_cache_acquire takes contiguous host tensors")
+                harr[i] = t.data_ptr()
+    darr = (ctypes.c_void_p * max(n, 1))()
+    sarr = (ctypes.c_int32 * max(n, 1))()
+    hitarr = (ctypes.c_int32 * max(n, 1))()
+    use_streams = host_blobs is not None
+    rc = lib().dz_cache_acquire(cache, n, karr, harr if host_blobs is not None else None, int(nbytes), darr, sarr, hitarr,
+                                _stream(copy_stream) if use_streams else None,
+                                _stream(compute_stream) if use_streams else None)
+    if rc != DZ_OK and check:
+        raise DzError(rc, "dz_cache_acquire")
+    return rc, [int(darr[i] or 0) for i in range(n)], [int(sarr[i]) for i in range(n)], [int(hitarr[i]) for i in range(n)]
+
+
+def dz_cache_stats(cache):
+    h, m, e = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    rc = lib().dz_cache_stats(cache, ctypes.byref(h), ctypes.byref(m), ctypes.byref(e))
+    if rc != DZ_OK:
+        raise DzError(rc, "dz_cache_stats")
+    return int(h.value), int(m.value), int(e.value)
 
 
 class Context:

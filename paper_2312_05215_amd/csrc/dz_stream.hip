@@ -148,12 +148,11 @@ __device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BI
     }
 }
 
-#ifndef DZ_RCAP_SMALL
-#define DZ_RCAP_SMALL 8
-#endif
-#ifndef DZ_DSTG_SMALL
-#define DZ_DSTG_SMALL 3
-#endif
+// Tuned constants of the one- and two-column-block shapes (T <= 32): k tiles of x an LDS round may
+// hold (8: 135 KB, one workgroup per CU) and packed-tile stage buffers of the delta phase (3: two
+// tiles in flight while one computes; 4 and 5 measured 1-4 % slower at eight waves per CU).
+constexpr int DZ_RCAP_SMALL = 8;
+constexpr int DZ_DSTG_SMALL = 3;
 template <int BITS, int GROUP, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int round_tiles)
@@ -162,8 +161,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     constexpr int SD = F::SD;
     constexpr int THREADS = WAVES * 64;
     constexpr int ZROW = 16 * J;            // an all-zero LDS row for column slots without a request
-    // packed-tile stage buffers of the delta phase (DSTG - 1 tiles in flight): as many as the
-    // register budget of the shape's occupancy allows
+    // packed-tile stage buffers of the delta phase (DSTG - 1 tiles in flight)
     constexpr int DSTG = (R == 1 && J <= 2) ? DZ_DSTG_SMALL : 5;
     extern __shared__ __attribute__((aligned(16))) _Float16 xs[];     // [16J + 1][LDW]
     __shared__ int s_tok[64];               // request row of each sorted position (-1: none)
@@ -610,9 +608,9 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group
     const int KT = a.K / 256;
     const int nchunks = (a.T + 63) / 64;
     const int J = (a.T >= 64) ? 4 : (a.T + 15) / 16;
-    // workgroup shape: few request columns -> 8 waves x 1 row tile (most waves in flight); three or
-    // four column blocks -> 4 waves x 2 row tiles (each B fragment read from LDS feeds two MFMAs,
-    // which the 2-bit format needs to stay under the LDS bandwidth)
+    // workgroup shape: one or two column blocks -> 8 waves x 1 row tile; three or four -> 4 waves x
+    // 2 row tiles (a packed tile's dequantisation set-up and each B fragment read from LDS serve two
+    // row tiles: measured 10-20 % faster there than 8 x 1)
     int WAVES = ctx->wg_waves, R = ctx->wg_rtiles;
     if (WAVES <= 0 || R <= 0) { WAVES = (J <= 2) ? 8 : 4; R = (J <= 2) ? 1 : 2; }
     // row blocks of the projections, one projection after the other; a row block never spans two
