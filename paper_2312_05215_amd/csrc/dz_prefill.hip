@@ -36,19 +36,21 @@ int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
 namespace {
 
 constexpr int PLDW = 256 + LDS_PAD; // LDS row stride in halfs (one k tile)
+constexpr int PFB = 2;              // column blocks by which the B fragment reads run ahead of their MFMAs
+                                    // (3 measured the same, 4 spills)
 
 // One base step (64 k) for R row tiles x J column blocks.  B fragments are read from LDS two
 // column blocks ahead of the MFMAs that use them: bq holds the fragments of blocks j and j + 1 on
 // entry and, when NEXT is set, those of blocks 0 and 1 of the following step on exit.
 template <int R, int J, bool NEXT>
 __device__ __forceinline__ void base_step(const u32x4 (&buf)[R][2], const _Float16 *xs, const Geo &g,
-                                          const int (&brow)[J], int kofs, f4 (&acc)[R][J], h16 (&bq)[2])
+                                          const int (&brow)[J], int kofs, f4 (&acc)[R][J], h16 (&bq)[PFB])
 {
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const h16 b = bq[j & 1];
-        if (j + 2 < J) bq[j & 1] = load_b(xs, brow[j + 2], g, kofs);
-        else if (NEXT) bq[j & 1] = load_b(xs, brow[j + 2 - J], g, kofs + 64);
+        const h16 b = bq[j % PFB];
+        if (j + PFB < J) bq[j % PFB] = load_b(xs, brow[j + PFB], g, kofs);
+        else if (NEXT) bq[j % PFB] = load_b(xs, brow[j + PFB - J], g, kofs + 64);
         const h8 b0 = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, 6, 7);
         const h8 b1 = __builtin_shufflevector(b, b, 8, 9, 10, 11, 12, 13, 14, 15);
 #pragma unroll
@@ -66,13 +68,13 @@ __device__ __forceinline__ void base_step(const u32x4 (&buf)[R][2], const _Float
 template <int R, int J, bool NEXT, int ODD>
 __device__ __forceinline__ void fused_step(const u32x4 (&buf)[R][2], const h8 (&av)[R], const uint32_t (&idxw)[R],
                                            const _Float16 *xs, const Geo &g, const int (&brow)[J], int kofs,
-                                           f4 (&acc)[R][J], h16 (&bq)[2])
+                                           f4 (&acc)[R][J], h16 (&bq)[PFB])
 {
 #pragma unroll
     for (int j = 0; j < J; ++j) {
-        const h16 b = bq[j & 1];
-        if (j + 2 < J) bq[j & 1] = load_b(xs, brow[j + 2], g, kofs);
-        else if (NEXT) bq[j & 1] = load_b(xs, brow[j + 2 - J], g, kofs + 64);
+        const h16 b = bq[j % PFB];
+        if (j + PFB < J) bq[j % PFB] = load_b(xs, brow[j + PFB], g, kofs);
+        else if (NEXT) bq[j % PFB] = load_b(xs, brow[j + PFB - J], g, kofs + 64);
         const h8 b0 = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, 6, 7);
         const h8 b1 = __builtin_shufflevector(b, b, 8, 9, 10, 11, 12, 13, 14, 15);
 #pragma unroll
@@ -370,9 +372,9 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
         if (whole) {
             for (int kt = kb; kt < ke; ++kt) {
                 const int ktn = min(kt + 1, ke - 1), ktnn = min(kt + 2, ke - 1);
-                h16 bq[2];
-                bq[0] = load_b(xcur, brow[0], g, 0);
-                bq[1] = load_b(xcur, brow[1], g, 0);
+                h16 bq[PFB];
+#pragma unroll
+                for (int u = 0; u < PFB; ++u) bq[u] = load_b(xcur, brow[u], g, 0);
 #define PF_FSTEP(st_, cur, nxt, xcurv, xnxtv)                                                                      \
     do {                                                                                                           \
         PF_XLOAD(xnxtv, (st_) < 3 ? ktn : ktnn, ((st_) + 1) & 3);                                                  \
@@ -405,10 +407,10 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
         // x slices fetched past the last k tile repeat it and land in the idle buffer
         const int ktn = min(kt + 1, ke - 1), ktnn = min(kt + 2, ke - 1);
         // ---- base: four steps of 64 k; each step also moves a quarter of the next x slice
-        h16 bq[2];
+        h16 bq[PFB];
         if constexpr (HAS_BASE) {
-            bq[0] = load_b(xcur, brow[0], g, 0);
-            bq[1] = load_b(xcur, brow[1], g, 0);
+#pragma unroll
+            for (int u = 0; u < PFB; ++u) bq[u] = load_b(xcur, brow[u], g, 0);
         }
         // one delta's packed tile: expand it into MFMA operands, request the next tile into the
         // freed stage buffer, multiply
