@@ -67,6 +67,21 @@ struct DzStreamArgs {
 };
 
 int dz_set_hip_error(dz_ctx *ctx, hipError_t e);
+
+// A kernel may use more than 64 KB of dynamic LDS only after an attribute has been set for it, once
+// per device.  `done` (one static word per kernel instantiation) remembers the devices it has been
+// set on; two threads racing here at worst set it twice, which is harmless.
+inline hipError_t dz_allow_lds(const void *kernel, int bytes, unsigned long long &done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done |= bit;
+    return e;
+}
 int dz_launch_pack(dz_ctx *, const uint8_t *, const uint8_t *, const void *, const void *, int, int,
                    int, int, void *, hipStream_t);
 int dz_launch_unpack(dz_ctx *, const void *, int, int, int, int, uint8_t *, uint8_t *, void *, void *,

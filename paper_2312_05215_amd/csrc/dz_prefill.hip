@@ -528,12 +528,9 @@ hipError_t launch_pf(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int 
 {
     auto k = prefill_kernel<BITS, GROUP, PW, PR, PJ, HB, HD>;
     const size_t lds = (size_t)(2 * 16 * PJ + 1) * PLDW * sizeof(_Float16);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static unsigned long long lds_allowed = 0;      // per instantiation
+    const hipError_t e = dz_allow_lds((const void *)k, (int)lds, lds_allowed);
+    if (e != hipSuccess) return e;
     const int tail = NRB * nchunks - 8 * a.max_slots;
     const int grid = 8 * (a.max_slots + ((tail + 7) / 8) * a.S);
     hipLaunchKernelGGL(k, dim3(grid), dim3(PW * 64), lds, st, a, dp, NRB, nchunks, L.off_idx, L.off_scale, L.total);

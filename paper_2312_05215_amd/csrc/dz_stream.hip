@@ -553,12 +553,9 @@ hipError_t launch_one(const DzStreamArgs &a, const DzGroup &gp, const DzGroupPtr
                       size_t lds, hipStream_t st)
 {
     auto k = stream_kernel<BITS, GROUP, WAVES, R, J, HB, HD>;
-    static bool attr_set = false;       // per instantiation; the attribute is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 8192);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static unsigned long long lds_allowed = 0;      // per instantiation
+    const hipError_t e = dz_allow_lds((const void *)k, 160 * 1024 - 8192, lds_allowed);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k, dim3(grid), dim3(WAVES * 64), lds, st, a, gp, dp, NRB, round_tiles);
     return hipGetLastError();
 }
