@@ -148,6 +148,7 @@ int dz_create(dz_ctx **out, int device)
     ctx->wg_rtiles = env_int("DZ_RTILES", 0);
     ctx->round_tiles = env_int("DZ_ROUND_TILES", 0);
     ctx->no_prefill = env_int("DZ_NO_PREFILL", 0);
+    ctx->tile_kernel = env_int("DZ_TILE", 1);
     DeviceGuard guard(device);
     hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
     if (e == hipSuccess) {

@@ -27,6 +27,7 @@ struct dz_ctx {
     int no_prefill;         // DZ_NO_PREFILL: serve large batches with the streaming kernel (chunks of 64 rows)
     int wg_waves, wg_rtiles; // DZ_WAVES, DZ_RTILES: workgroup shape of the streaming kernel
     int num_cus;            // compute units of the device
+    int tile_kernel;        // DZ_TILE (default 1): the base product of large batches goes to the 256 x 256 tile kernel
 };
 
 #define DZ_SEG_MAX_D 8192
@@ -90,3 +91,5 @@ int dz_launch_segment(dz_ctx *, const int32_t *ids, int T, int D, int32_t *count
                       int32_t *perm, int32_t *key, hipStream_t);
 int dz_launch_stream(dz_ctx *, const DzStreamArgs &, const DzGroup &, const DzGroupPtrs &, hipStream_t);
 int dz_launch_prefill(dz_ctx *, const DzStreamArgs &, const DzDeltaPtrs &, hipStream_t);
+int dz_launch_tile(dz_ctx *, const DzStreamArgs &, hipStream_t);
+bool dz_tile_fits(const DzStreamArgs &);

@@ -595,6 +595,7 @@ int dz_launch_prefill(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &
     DzStreamArgs a = args;
     if ((unsigned long long)a.N * a.K * 2ull >= (1ull << 32)) return DZ_ERR_SHAPE;     // 32-bit byte offsets
     if ((unsigned long long)a.T * a.K * 2ull >= (1ull << 31)) return DZ_ERR_SHAPE;     // x offsets, bit 31 = no row
+    if (ctx->tile_kernel && dz_tile_fits(a)) return dz_launch_tile(ctx, a, st);
     DzLayout L = dz_make_layout(a.N, a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
     hipError_t e;
     int rc = DZ_OK;

@@ -164,3 +164,26 @@ def test_tiles_of_one_delta(dz):
         rng.shuffle(ids2)
         cs = Case(dz, c.h, 22, T, N, K, D, 4, 128, ids2)
         _run_all(dz, c, cs, "mixed tiles")
+
+
+@pytest.mark.parametrize("env", [{}, {"DZ_SPLITS": "3"}, {"DZ_TILE": "0"}], ids=["auto", "splits3", "narrow_tiles"])
+def test_base_gemm_of_a_large_batch_over_several_tiles(dz, env):
+    """The base product of a large batch (Eq. (2), first term): several 256 x 256 tiles with ragged
+    last tiles in both directions, whole and cut into k slices, and the narrower tile kernel."""
+    import oracle
+    T, N, K = 600, 784, 1024
+    print(f"wide base gemm {env}", flush=True)
+    for k, v in env.items():
+        os.environ[k] = v
+    try:
+        with dz.Context(0) as c:
+            W = S.make_base(N, K, S.stream(70, "W"), 0.02)
+            x = S.make_x(T, K, S.stream(70, "x"))
+            ref = oracle.c.linear(x.numpy(), W.numpy(), None, None)
+            o = torch.full((T, N), 7.0, dtype=torch.float16, device="cuda")
+            dz.dz_base_gemm(c.h, x.cuda(), W.cuda(), o, T, N, K)
+            assert dz.dz_check(c.h) == dz.DZ_OK
+            assert_close(o, ref, f"base gemm {env}")
+    finally:
+        for k in env:
+            os.environ.pop(k, None)
