@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-group", action="store_true",
                     help="one dz_linear call per projection instead of one dz_linear_group call for q,k,v and one for gate,up")
+    ap.add_argument("--path", default="linear", choices=["linear", "base", "sbmm"],
+                    help="which part of the layer is timed: the fused layer (default, the headline figure), "
+                         "dz_base_gemm alone or dz_sbmm alone (one call per projection; for kernel profiles)")
     ap.add_argument("--graph", action="store_true",
                     help="record the step's launches into a HIP graph once and time its replays")
     ap.add_argument("--no-compare", action="store_true",
@@ -124,8 +127,19 @@ def main():
                     dz.dz_linear_group(ctx.h, sel[0][4], [r[2] for r in sel], [r[3] for r in sel], d_ids,
                                        [r[5] for r in sel], cfg.T, [r[0] for r in sel], sel[0][1], cfg.bits, cfg.group)
 
-    grouped = not args.no_group
+    def step_part():
+        for row in layers:
+            for N, K, W, packed, x, out in row:
+                if args.path == "base":
+                    dz.dz_base_gemm(ctx.h, x, W, out, cfg.T, N, K)
+                else:
+                    dz.dz_sbmm(ctx.h, x, packed, d_ids, out, cfg.T, N, K, cfg.bits, cfg.group, 0)
+
+    grouped = not args.no_group and args.path == "linear"
     step = step_grouped if grouped else step_single
+    if args.path != "linear":
+        step = step_part
+        args.no_compare = True
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -166,7 +180,9 @@ def main():
     tokens_per_s = cfg.T / (ms_model * 1e-3)
 
     launches_per_step = n_layers * (len(groups) if grouped else len(projs))
-    bytes_per_step = n_layers * sum(S.algorithmic_bytes(N, K, cfg.T, cfg.bits, cfg.group, n_active) for _, N, K in projs)
+    act = 0 if args.path == "base" else n_active
+    bytes_per_step = n_layers * sum(S.algorithmic_bytes(N, K, cfg.T, cfg.bits, cfg.group, act) - (2 * N * K if args.path == "sbmm" else 0)
+                                    for _, N, K in projs)
     avg_launch_us = ms_per_step * 1e3 / launches_per_step
     achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
     # measured HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/);
@@ -190,9 +206,13 @@ def main():
         # large batches run the tiled MFMA kernel: 2*T*N*K flops of the base product plus 2*T*N*K/2 of the
         # 2:4-sparse delta product for every request row that names a delta
         rows_with_delta = int(((ids >= 0) & (ids < cfg.D)).sum())
-        flops_per_step = n_layers * sum(2.0 * N * K * (cfg.T + 0.5 * rows_with_delta) for _, N, K in projs)
+        dense_rows = 0 if args.path == "sbmm" else cfg.T
+        sparse_rows = 0 if args.path == "base" else rows_with_delta
+        flops_per_step = n_layers * sum(2.0 * N * K * (dense_rows + 0.5 * sparse_rows) for _, N, K in projs)
         tf = flops_per_step / (ms_per_step * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "prefill_kernel (fused base GEMM + SBMM)", "achieved": round(tf, 1),
+        kname = {"linear": "prefill_kernel (fused base GEMM + SBMM)", "base": "tile_kernel (base GEMM)",
+                 "sbmm": "prefill_kernel (SBMM)"}[args.path]
+        roofline = {"bound": "mfma", "kernel": kname, "achieved": round(tf, 1),
                     "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4),
                     "traffic": None, "flops_per_launch_avg": int(flops_per_step // launches_per_step),
                     "avg_launch_us": round(avg_launch_us, 2), "launches_per_step": launches_per_step}
@@ -228,6 +248,8 @@ def main():
                    "deltas": cfg.D, "active_deltas": n_active, "bits": cfg.bits, "group": cfg.group,
                    "projections_per_layer": len(projs), "launches_per_layer": len(groups) if grouped else len(projs),
                    "grouping": "q,k,v in one call; gate,up in one call" if grouped else "one call per projection",
+                   "path": {"linear": "fused layer (dz_linear / dz_linear_group)", "base": "dz_base_gemm only",
+                            "sbmm": "dz_sbmm only"}[args.path],
                    "submission": "replays of one HIP graph of the step" if args.graph else "eager launches",
                    "gen_seconds": round(gen_s, 1)},
         ("ms_per_step_one_call_per_projection" if grouped else "ms_per_step_grouped"):
