@@ -27,7 +27,8 @@ struct dz_ctx {
     int no_prefill;         // DZ_NO_PREFILL: serve large batches with the streaming kernel (chunks of 64 rows)
     int wg_waves, wg_rtiles; // DZ_WAVES, DZ_RTILES: workgroup shape of the streaming kernel
     int num_cus;            // compute units of the device
-    int tile_kernel;        // DZ_TILE (default 1): the base product of large batches goes to the 256 x 256 tile kernel
+    int tile_kernel;        // DZ_TILE: 1 (default) = the base product of large batches goes to the 256 x 256 tile
+                            // kernel when it has enough tiles, 2 = always, 0 = never
 };
 
 #define DZ_SEG_MAX_D 8192

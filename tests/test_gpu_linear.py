@@ -166,10 +166,12 @@ def test_tiles_of_one_delta(dz):
         _run_all(dz, c, cs, "mixed tiles")
 
 
-@pytest.mark.parametrize("env", [{}, {"DZ_SPLITS": "3"}, {"DZ_TILE": "0"}], ids=["auto", "splits3", "narrow_tiles"])
+@pytest.mark.parametrize("env", [{"DZ_TILE": "2"}, {"DZ_TILE": "2", "DZ_SPLITS": "3"}, {"DZ_TILE": "2", "DZ_SPLITS": "1"}, {}],
+                         ids=["wide", "wide_splits3", "wide_whole", "default"])
 def test_base_gemm_of_a_large_batch_over_several_tiles(dz, env):
     """The base product of a large batch (Eq. (2), first term): several 256 x 256 tiles with ragged
-    last tiles in both directions, whole and cut into k slices, and the narrower tile kernel."""
+    last tiles in both directions, whole and cut into k slices (DZ_TILE=2 sends every such call to
+    the 256 x 256 kernel, which by default only takes calls with many tiles), and the default route."""
     import oracle
     T, N, K = 600, 784, 1024
     print(f"wide base gemm {env}", flush=True)
