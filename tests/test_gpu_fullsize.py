@@ -64,3 +64,23 @@ def test_fullsize_sampled_rows(dz, cfgname, N, K):
         # the delta term really is in there: compare against the base-only oracle too
         ref_base = oracle.c.linear(xn, Wn, None, None)
         assert np.abs(ref - ref_base).max() > 10 * np.abs(got.float().cpu().numpy() - ref).max()
+
+
+@pytest.mark.parametrize("N,K", [(5120, 5120), (13824, 5120), (5120, 13824)], ids=lambda v: str(v))
+def test_fullsize_base_product_of_the_prefill_batch(dz, N, K):
+    """dz_base_gemm alone at the prefill workload's sizes (the route bench.py --path base times: the
+    256 x 256 tile kernel where it has enough tiles), sampled output features against the oracle."""
+    print(f"case 13b_prefill base {N}x{K}", flush=True)
+    cfg = S.config("13b_prefill")
+    with dz.Context(0) as c:
+        W = S.make_base(N, K, S.stream(3, "W", N, K), 0.02).cuda()
+        x = S.make_x(cfg.T, K, S.stream(3, "x", K)).cuda()
+        out = torch.full((cfg.T, N), 7.0, dtype=torch.float16, device="cuda")
+        dz.dz_base_gemm(c.h, x, W, out, cfg.T, N, K)
+        assert dz.dz_check(c.h) == dz.DZ_OK
+        assert torch.isfinite(out.float()).all()
+        rows = _sample_rows(N)
+        ridx = torch.as_tensor(rows, device="cuda")
+        ref = oracle.c.linear(x.cpu().numpy(), W[ridx].cpu().numpy(), None, None)
+        max_rel, mean_abs = assert_close(out[:, ridx], ref, f"base {N}x{K}")
+        print(f"  max_rel={max_rel:.2e} mean_abs={mean_abs:.2e}", flush=True)
