@@ -5,8 +5,9 @@
 // What bounds a tiled kernel on this chip is the operand bytes a CU has to bring in per flop (a CU
 // keeps only so many cache lines in flight, and they arrive with HBM latency), so the tile is as
 // large as the registers allow and both operands travel the cheapest way:
-//   * a workgroup (8 waves) owns 256 rows of N x 256 request rows and walks k in steps of 64; a
-//     wave owns 2 row tiles x 16 column blocks = 32 accumulator tiles (128 registers);
+//   * a workgroup (8 waves, 4 x 2) owns 256 rows of N x 256 request rows and walks k in steps of
+//     64; a wave owns 4 row tiles x 8 column blocks = 32 accumulator tiles (128 registers), the
+//     squarest wave tile, which needs the fewest fragment bytes from LDS per MFMA;
 //   * the W and x slices of a step are fetched with row-contiguous 16-byte loads (whole cache lines
 //     per instruction), parked in registers for one step and written to LDS, double buffered, one
 //     barrier per step; A and B fragments of the MFMAs are read from LDS, B two column blocks
@@ -23,11 +24,12 @@ int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
 namespace {
 
 constexpr int TLD = 64 + LDS_PAD;   // LDS row stride in halfs of a 64-k slice
-constexpr int TW = 8;               // waves
-constexpr int TRT = 2;              // row tiles per wave
-constexpr int TJ = 16;              // column blocks per wave (all of the tile's)
-constexpr int TROWS = TW * TRT * 16;    // 256 rows of N per tile
-constexpr int TCH = TJ * 16;            // 256 request rows per tile
+constexpr int TWR = 4, TWC = 2;     // waves along the rows of N and along the request rows
+constexpr int TW = TWR * TWC;       // 8 waves
+constexpr int TRT = 4;              // row tiles per wave
+constexpr int TJ = 8;               // column blocks per wave
+constexpr int TROWS = TWR * TRT * 16;   // 256 rows of N per tile
+constexpr int TCH = TWC * TJ * 16;      // 256 request rows per tile
 constexpr int TTHREADS = TW * 64;
 
 __global__ __launch_bounds__(TTHREADS) void tile_kernel(DzStreamArgs a, int NRB, int nchunks)
@@ -43,6 +45,7 @@ __global__ __launch_bounds__(TTHREADS) void tile_kernel(DzStreamArgs a, int NRB,
     g.KT = a.K >> 8;
     g.LDW = TLD;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave % TWR, wc = wave / TWR;     // this wave's block of rows and of request rows
 
     // tile of this workgroup: as in the narrower tiled kernel (whole tiles first, XCD by XCD, then
     // the tiles of the last round cut into S slices of k)
@@ -71,7 +74,7 @@ __global__ __launch_bounds__(TTHREADS) void tile_kernel(DzStreamArgs a, int NRB,
     bool rvalid[TRT];
 #pragma unroll
     for (int r = 0; r < TRT; ++r) {
-        const int rt = rb * (TW * TRT) + wave * TRT + r;
+        const int rt = rb * (TWR * TRT) + wr * TRT + r;
         rvalid[r] = rt < RT;
         rtc[r] = rvalid[r] ? rt : RT - 1;
     }
@@ -116,8 +119,8 @@ __global__ __launch_bounds__(TTHREADS) void tile_kernel(DzStreamArgs a, int NRB,
     TK_STORE(0);
     TK_LOAD(min(s_first + 1, s_final));
 
-    const int aoff = (wave * TRT * 16 + g.row) * TLD + g.q * 8;
-    const int boff = g.row * TLD;
+    const int aoff = (wr * TRT * 16 + g.row) * TLD + g.q * 8;
+    const int boff = (wc * TJ * 16 + g.row) * TLD;
     // One step: publish the next slice, request the one after, multiply the current one.
     for (int step = s_first; step <= s_final; ++step) {
         const int buf = (step - s_first) & 1;
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(TTHREADS) void tile_kernel(DzStreamArgs a, int NRB,
         if (!rvalid[r]) continue;
 #pragma unroll
         for (int j = 0; j < TJ; ++j) {
-            const int tok = p0 + 16 * j + g.row;
+            const int tok = p0 + (wc * TJ + j) * 16 + g.row;
             if (tok < a.T) store_row4(out + (size_t)tok * a.N + rtc[r] * 16 + 4 * g.q, acc[r][j], a.accumulate);
         }
     }
