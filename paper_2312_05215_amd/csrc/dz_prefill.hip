@@ -596,12 +596,12 @@ int dz_launch_prefill(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &
     if ((unsigned long long)a.N * a.K * 2ull >= (1ull << 32)) return DZ_ERR_SHAPE;     // 32-bit byte offsets
     if ((unsigned long long)a.T * a.K * 2ull >= (1ull << 31)) return DZ_ERR_SHAPE;     // x offsets, bit 31 = no row
     // The base product alone goes to the 256 x 256 tile kernel when that leaves enough tiles to keep
-    // most CUs busy (measured: faster from about 0.6 tiles per CU on, slower below); DZ_TILE=2 sends
+    // enough CUs busy (measured: faster from about 0.3 tiles per CU on, slower below); DZ_TILE=2 sends
     // every such call there, DZ_TILE=0 none.
     if (ctx->tile_kernel && dz_tile_fits(a)) {
         const long long wide_tiles = (long long)((a.N + 255) / 256) * ((a.T + 255) / 256);
         const int cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
-        if (ctx->tile_kernel > 1 || wide_tiles * 10 >= (long long)cus * 6) return dz_launch_tile(ctx, a, st);
+        if (ctx->tile_kernel > 1 || wide_tiles * 10 >= (long long)cus * 3) return dz_launch_tile(ctx, a, st);
     }
     DzLayout L = dz_make_layout(a.N, a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
     hipError_t e;

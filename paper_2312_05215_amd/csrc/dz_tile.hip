@@ -8,10 +8,14 @@
 //   * a workgroup (8 waves, 4 x 2) owns 256 rows of N x 256 request rows and walks k in steps of
 //     64; a wave owns 4 row tiles x 8 column blocks = 32 accumulator tiles (128 registers), the
 //     squarest wave tile, which needs the fewest fragment bytes from LDS per MFMA;
-//   * the W and x slices of a step are fetched with row-contiguous 16-byte loads (whole cache lines
-//     per instruction), parked in registers for one step and written to LDS, double buffered, one
-//     barrier per step; A and B fragments of the MFMAs are read from LDS, B two column blocks
-//     ahead of the MFMAs that use it;
+//   * the W and x slices of a step go from global memory straight into LDS (buffer loads with an
+//     LDS destination: no staging registers, no LDS store instructions), double buffered, one
+//     barrier per step.  Such a load writes the 64 lanes' 16-byte pieces side by side, so LDS rows
+//     are unpadded 128-byte runs; to keep fragment reads off one bank set, slot s of row r holds
+//     piece s ^ ((r >> 1) & 7) of the row -- the swizzle is applied to the global address a lane
+//     fetches, and again by the lanes that read fragments.  A wave's load covers 8 rows x 128
+//     bytes: whole cache lines.  A and B fragments of the MFMAs are read from LDS, B two column
+//     blocks ahead of the MFMAs that use it;
 //   * the tiles of the last, partly filled round of one-tile-per-CU are cut into k slices that
 //     meet in fp32, as in the narrower tiled kernel.
 // Fused and delta-only calls stay with the narrower kernel: with 128 registers of accumulators the
@@ -23,7 +27,7 @@ int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
 
 namespace {
 
-constexpr int TLD = 64 + LDS_PAD;   // LDS row stride in halfs of a 64-k slice
+constexpr int TLD = 64;             // LDS row stride in halfs of a 64-k slice (no padding: see the swizzle)
 constexpr int TWR = 4, TWC = 2;     // waves along the rows of N and along the request rows
 constexpr int TW = TWR * TWC;       // 8 waves
 constexpr int TRT = 4;              // row tiles per wave
@@ -84,67 +88,67 @@ __global__ __launch_bounds__(TTHREADS) void tile_kernel(DzStreamArgs a, int NRB,
 #pragma unroll
         for (int j = 0; j < TJ; ++j) acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
 
-    // ---- staging of the W and x slices: piece u of a thread is row u * 64 + tid / 8, bytes
-    // 16 * (tid % 8) of the slice, so a wave's load covers 8 rows x 128 bytes.  Rows that do not
-    // exist get an offset beyond the resource, which the hardware answers with zeros.
+    // ---- the W and x slices: piece u of a thread is row u * 64 + tid / 8 of the slice, LDS slot
+    // tid % 8 of that row, which holds global piece (tid % 8) ^ ((row >> 1) & 7).  A wave's 64
+    // lanes cover 8 consecutive rows = 1 KB of LDS in lane order, as the LDS-destination load
+    // writes it.  Rows that do not exist get an offset beyond the resource (the hardware reads
+    // zeros; whatever lands in LDS for them only reaches output rows that are never stored).
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(a.W, (uint32_t)a.N * (uint32_t)a.K * 2u);
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (uint32_t)a.T * (uint32_t)a.K * 2u);
     uint32_t woff[4], xoff[4];
-    const int sdst = (tid >> 3) * TLD + (tid & 7) * 8;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int r = u * 64 + (tid >> 3);
+        const uint32_t c = (uint32_t)((tid & 7) ^ ((r >> 1) & 7)) * 16u;
         const int n = rb * TROWS + r, t = p0 + r;
-        woff[u] = n < a.N ? (uint32_t)n * (uint32_t)a.K * 2u + (uint32_t)(tid & 7) * 16u : 0x80000000u;
-        xoff[u] = t < a.T ? (uint32_t)t * (uint32_t)a.K * 2u + (uint32_t)(tid & 7) * 16u : 0x80000000u;
+        woff[u] = n < a.N ? (uint32_t)n * (uint32_t)a.K * 2u + c : 0x80000000u;
+        xoff[u] = t < a.T ? (uint32_t)t * (uint32_t)a.K * 2u + c : 0x80000000u;
     }
-    u32x4 wv[4], xv[4];
-#define TK_LOAD(step)                                                                                              \
+    typedef __attribute__((address_space(3))) void lds_void;
+#define TK_LOAD(buf, step)                                                                                         \
     do {                                                                                                           \
-        _Pragma("unroll") for (int u = 0; u < 4; ++u)                                                             \
-            wv[u] = __builtin_amdgcn_raw_buffer_load_b128(rw, woff[u], (uint32_t)(step) * 128u, 0);                \
-        _Pragma("unroll") for (int u = 0; u < 4; ++u)                                                             \
-            xv[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, xoff[u], (uint32_t)(step) * 128u, 0);                \
-    } while (0)
-#define TK_STORE(buf)                                                                                              \
-    do {                                                                                                           \
-        _Pragma("unroll") for (int u = 0; u < 4; ++u)                                                             \
-            *(u32x4 *)(ws + (buf) * TROWS * TLD + sdst + u * 64 * TLD) = wv[u];                                    \
-        _Pragma("unroll") for (int u = 0; u < 4; ++u)                                                             \
-            *(u32x4 *)(xs + (buf) * TCH * TLD + sdst + u * 64 * TLD) = xv[u];                                      \
+        _Pragma("unroll") for (int u = 0; u < 4; ++u) {                                                           \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_void *)(ws + (buf) * TROWS * TLD + (u * 64 + wave * 8) * TLD), \
+                                                     16, woff[u], (uint32_t)(step) * 128u, 0, 0);                  \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void *)(xs + (buf) * TCH * TLD + (u * 64 + wave * 8) * TLD),   \
+                                                     16, xoff[u], (uint32_t)(step) * 128u, 0, 0);                  \
+        }                                                                                                          \
     } while (0)
 
     const int s_first = 4 * kb, s_final = 4 * ke - 1;
-    TK_LOAD(s_first);
-    TK_STORE(0);
-    TK_LOAD(min(s_first + 1, s_final));
+    TK_LOAD(0, s_first);
 
-    const int aoff = (wr * TRT * 16 + g.row) * TLD + g.q * 8;
+    const int sw = (g.row >> 1) & 7;                 // swizzle of this lane's fragment rows (row & 15 decides it)
+    const int f0 = (g.q ^ sw) * 8, f1 = ((g.q + 4) ^ sw) * 8;      // slots of k 8q.. and 32 + 8q.. (halfs)
+    const int aoff = (wr * TRT * 16 + g.row) * TLD;
     const int boff = (wc * TJ * 16 + g.row) * TLD;
-    // One step: publish the next slice, request the one after, multiply the current one.
+    // One step: wait for the slice, request the next one into the other buffer, multiply.
     for (int step = s_first; step <= s_final; ++step) {
         const int buf = (step - s_first) & 1;
-        lds_barrier();                               // slice `step` is complete, slice step - 1 no longer read
-        TK_STORE(buf ^ 1);                           // slice step + 1
-        TK_LOAD(min(step + 2, s_final));
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's pieces of slice `step` are in LDS
+        lds_barrier();                               // everybody's are, and slice step - 1 is no longer read
+        TK_LOAD(buf ^ 1, min(step + 1, s_final));
         __builtin_amdgcn_sched_barrier(0);
         const _Float16 *wb = ws + buf * TROWS * TLD;
         const _Float16 *xb = xs + buf * TCH * TLD;
         h8 af[TRT][2];
 #pragma unroll
         for (int r = 0; r < TRT; ++r) {
-            af[r][0] = *(const h8 *)(wb + aoff + r * 16 * TLD);
-            af[r][1] = *(const h8 *)(wb + aoff + r * 16 * TLD + 32);
+            af[r][0] = *(const h8 *)(wb + aoff + r * 16 * TLD + f0);
+            af[r][1] = *(const h8 *)(wb + aoff + r * 16 * TLD + f1);
         }
-        h16 bq[2];
-        bq[0] = load_b(xb, boff, g, 0);
-        bq[1] = load_b(xb, boff + 16 * TLD, g, 0);
+        h8 bq[2][2];
+        bq[0][0] = *(const h8 *)(xb + boff + f0);
+        bq[0][1] = *(const h8 *)(xb + boff + f1);
+        bq[1][0] = *(const h8 *)(xb + boff + 16 * TLD + f0);
+        bq[1][1] = *(const h8 *)(xb + boff + 16 * TLD + f1);
 #pragma unroll
         for (int j = 0; j < TJ; ++j) {
-            const h16 b = bq[j & 1];
-            if (j + 2 < TJ) bq[j & 1] = load_b(xb, boff + (j + 2) * 16 * TLD, g, 0);
-            const h8 b0 = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, 6, 7);
-            const h8 b1 = __builtin_shufflevector(b, b, 8, 9, 10, 11, 12, 13, 14, 15);
+            const h8 b0 = bq[j & 1][0], b1 = bq[j & 1][1];
+            if (j + 2 < TJ) {
+                bq[j & 1][0] = *(const h8 *)(xb + boff + (j + 2) * 16 * TLD + f0);
+                bq[j & 1][1] = *(const h8 *)(xb + boff + (j + 2) * 16 * TLD + f1);
+            }
 #pragma unroll
             for (int r = 0; r < TRT; ++r) {
                 acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[r][0], b0, acc[r][j], 0, 0, 0);
@@ -153,8 +157,8 @@ __global__ __launch_bounds__(TTHREADS) void tile_kernel(DzStreamArgs a, int NRB,
             __builtin_amdgcn_sched_barrier(0);       // keep the reads two blocks ahead of their MFMAs
         }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // the last, redundant request has landed too
 #undef TK_LOAD
-#undef TK_STORE
 
     // ---- k slices of one tile meet in fp32 (as in the narrower tiled kernel): every slice stores
     // its accumulators with agent-scope stores, waits for them and bumps the tile's arrival
