@@ -122,41 +122,45 @@ __global__ __launch_bounds__(TTHREADS) void tile_kernel(DzStreamArgs a, int NRB,
     const int f0 = (g.q ^ sw) * 8, f1 = ((g.q + 4) ^ sw) * 8;      // slots of k 8q.. and 32 + 8q.. (halfs)
     const int aoff = (wr * TRT * 16 + g.row) * TLD;
     const int boff = (wc * TJ * 16 + g.row) * TLD;
-    // One step: wait for the slice, request the next one into the other buffer, multiply.
-    for (int step = s_first; step <= s_final; ++step) {
-        const int buf = (step - s_first) & 1;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's pieces of slice `step` are in LDS
-        lds_barrier();                               // everybody's are, and slice step - 1 is no longer read
-        TK_LOAD(buf ^ 1, min(step + 1, s_final));
-        __builtin_amdgcn_sched_barrier(0);
-        const _Float16 *wb = ws + buf * TROWS * TLD;
-        const _Float16 *xb = xs + buf * TCH * TLD;
-        h8 af[TRT][2];
-#pragma unroll
-        for (int r = 0; r < TRT; ++r) {
-            af[r][0] = *(const h8 *)(wb + aoff + r * 16 * TLD + f0);
-            af[r][1] = *(const h8 *)(wb + aoff + r * 16 * TLD + f1);
-        }
-        h8 bq[2][2];
-        bq[0][0] = *(const h8 *)(xb + boff + f0);
-        bq[0][1] = *(const h8 *)(xb + boff + f1);
-        bq[1][0] = *(const h8 *)(xb + boff + 16 * TLD + f0);
-        bq[1][1] = *(const h8 *)(xb + boff + 16 * TLD + f1);
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) {
-            const h8 b0 = bq[j & 1][0], b1 = bq[j & 1][1];
-            if (j + 2 < TJ) {
-                bq[j & 1][0] = *(const h8 *)(xb + boff + (j + 2) * 16 * TLD + f0);
-                bq[j & 1][1] = *(const h8 *)(xb + boff + (j + 2) * 16 * TLD + f1);
-            }
-#pragma unroll
-            for (int r = 0; r < TRT; ++r) {
-                acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[r][0], b0, acc[r][j], 0, 0, 0);
-                acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[r][1], b1, acc[r][j], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);       // keep the reads two blocks ahead of their MFMAs
-        }
+    // One step: wait for the slice, request the next one into the other buffer, multiply.  A
+    // workgroup walks a multiple of four steps, so the loop is unrolled by two and the buffer of a
+    // step is known at compile time (all LDS addresses become immediates).
+#define TK_STEP(BUF, step)                                                                                         \
+    do {                                                                                                           \
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  /* this wave's pieces of slice `step` are in LDS */      \
+        lds_barrier();                       /* everybody's are, and slice step - 1 is no longer read */           \
+        TK_LOAD((BUF) ^ 1, min((step) + 1, s_final));                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        const _Float16 *wb = ws + (BUF) * TROWS * TLD;                                                             \
+        const _Float16 *xb = xs + (BUF) * TCH * TLD;                                                               \
+        h8 af[TRT][2];                                                                                             \
+        _Pragma("unroll") for (int r = 0; r < TRT; ++r) {                                                         \
+            af[r][0] = *(const h8 *)(wb + aoff + r * 16 * TLD + f0);                                               \
+            af[r][1] = *(const h8 *)(wb + aoff + r * 16 * TLD + f1);                                               \
+        }                                                                                                          \
+        h8 bq[2][2];                                                                                               \
+        bq[0][0] = *(const h8 *)(xb + boff + f0);                                                                  \
+        bq[0][1] = *(const h8 *)(xb + boff + f1);                                                                  \
+        bq[1][0] = *(const h8 *)(xb + boff + 16 * TLD + f0);                                                       \
+        bq[1][1] = *(const h8 *)(xb + boff + 16 * TLD + f1);                                                       \
+        _Pragma("unroll") for (int j = 0; j < TJ; ++j) {                                                          \
+            const h8 b0 = bq[j & 1][0], b1 = bq[j & 1][1];                                                         \
+            if (j + 2 < TJ) {                                                                                      \
+                bq[j & 1][0] = *(const h8 *)(xb + boff + (j + 2) * 16 * TLD + f0);                                 \
+                bq[j & 1][1] = *(const h8 *)(xb + boff + (j + 2) * 16 * TLD + f1);                                 \
+            }                                                                                                      \
+            _Pragma("unroll") for (int r = 0; r < TRT; ++r) {                                                     \
+                acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[r][0], b0, acc[r][j], 0, 0, 0);              \
+                acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[r][1], b1, acc[r][j], 0, 0, 0);              \
+            }                                                                                                      \
+            __builtin_amdgcn_sched_barrier(0);   /* keep the reads two blocks ahead of their MFMAs */               \
+        }                                                                                                          \
+    } while (0)
+    for (int step = s_first; step <= s_final; step += 2) {
+        TK_STEP(0, step);
+        TK_STEP(1, step + 1);
     }
+#undef TK_STEP
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // the last, redundant request has landed too
 #undef TK_LOAD
 
