@@ -148,11 +148,12 @@ __device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BI
     }
 }
 
-// Tuned constants of the one- and two-column-block shapes (T <= 32): k tiles of x an LDS round may
-// hold (8: 135 KB, one workgroup per CU) and packed-tile stage buffers of the delta phase (3: two
-// tiles in flight while one computes; 4 and 5 measured 1-4 % slower at eight waves per CU).
+// Tuned constants: k tiles of x an LDS round may hold for the one- and two-column-block shapes
+// (T <= 32; 8: 135 KB, one workgroup per CU), and packed-tile stage buffers of the delta phase (3:
+// two tiles in flight while one computes; 4 and 5 measured 1-7 % slower on every shape at eight
+// waves per CU).
 constexpr int DZ_RCAP_SMALL = 8;
-constexpr int DZ_DSTG_SMALL = 3;
+constexpr int DSTG = 3;
 template <int BITS, int GROUP, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int round_tiles)
@@ -161,8 +162,6 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     constexpr int SD = F::SD;
     constexpr int THREADS = WAVES * 64;
     constexpr int ZROW = 16 * J;            // an all-zero LDS row for column slots without a request
-    // packed-tile stage buffers of the delta phase (DSTG - 1 tiles in flight)
-    constexpr int DSTG = (R == 1 && J <= 2) ? DZ_DSTG_SMALL : 5;
     extern __shared__ __attribute__((aligned(16))) _Float16 xs[];     // [16J + 1][LDW]
     __shared__ int s_tok[64];               // request row of each sorted position (-1: none)
     __shared__ int s_key[64];               // delta of each sorted position
@@ -282,7 +281,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         // named stage buffers (so each stays in registers), rotated by hand.  Issue cursors stop at
         // the last task / step and re-issue it (a few redundant cache hits at the end of a round)
         // so that issuing needs no branch.
-        uint32_t st0[R][SD], st1[R][SD], st2[R][SD], st3[R][SD], st4[R][SD];
+        uint32_t st0[R][SD], st1[R][SD], st2[R][SD];
         u32x4 bw0[R][2], bw1[R][2], bw2[R][2], bw3[R][2];
         uint32_t wbase[R];
 #pragma unroll
@@ -427,8 +426,6 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             }
             DZ_ISSUE(st0);
             DZ_ISSUE(st1);
-            if constexpr (DSTG >= 4) DZ_ISSUE(st2);
-            if constexpr (DSTG >= 5) DZ_ISSUE(st3);
         }
         DZ_XSTORE();
         lds_barrier();
@@ -447,22 +444,10 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             task_setup<J>(cc, kr0, tab, brow, ZROW * g.LDW, g, tk);
             task_frags<J>(tk, xs, g, 0, bq);
             while (tc < nd) {
-                if constexpr (DSTG == 3) {
-                    DZ_STEP(st0, st2);
-                    DZ_STEP(st1, st0);
-                    DZ_STEP(st2, st1);
-                } else if constexpr (DSTG == 4) {
-                    DZ_STEP(st0, st3);
-                    DZ_STEP(st1, st0);
-                    DZ_STEP(st2, st1);
-                    DZ_STEP(st3, st2);
-                } else {
-                    DZ_STEP(st0, st4);
-                    DZ_STEP(st1, st0);
-                    DZ_STEP(st2, st1);
-                    DZ_STEP(st3, st2);
-                    DZ_STEP(st4, st3);
-                }
+                static_assert(DSTG == 3, "the rotation below is written for three stage buffers");
+                DZ_STEP(st0, st2);
+                DZ_STEP(st1, st0);
+                DZ_STEP(st2, st1);
             }
         }
 #undef DZ_ISSUE
