@@ -126,3 +126,31 @@ def test_transposed_operand_would_fail():
     assert y.shape == (T, N)
     for n in range(N):
         assert y[0, n] == float(W[n, 5]) and y[1, n] == 2 * float(W[n, 0]) and y[2, n] == -float(W[n, 15])
+
+
+@pytest.mark.parametrize("impl", ["c", "np"])
+def test_fp16_subnormal_weights_are_widened_exactly(impl):
+    """About 0.2 % of base weights drawn from N(0, 0.02) are fp16 subnormals (|w| < 2^-14).  A one-hot
+    activation picks single weights out, so every subnormal bit pattern, both signs, must come back as
+    exactly m * 2^-24 -- no tolerance: a wrong exponent in the widening of subnormals cannot hide."""
+    pats = np.concatenate([np.arange(1, 1024, dtype=np.uint16), np.arange(1, 1024, dtype=np.uint16) | 0x8000])
+    N, K = pats.size, 8
+    W = np.zeros((N, K), np.uint16)
+    W[:, 3] = pats
+    W[:, 5] = 0x3C00                    # 1.0 in a column the activation does not select
+    W = W.view(np.float16)
+    x = np.zeros((2, K), np.float16)
+    x[0, 3] = 1.0
+    x[1, 3] = -2.0
+    lin = oracle.c.linear if impl == "c" else oracle.np_.linear
+    y = lin(x, W, None, None)
+    m = (pats & 0x3FF).astype(np.float64) * np.where(pats & 0x8000, -1.0, 1.0)
+    want = m * 2.0 ** -24               # exact in binary64 and in binary32
+    assert y.dtype == np.float32
+    assert (y[0].astype(np.float64) == want).all()
+    assert (y[1].astype(np.float64) == -2.0 * want).all()
+    # a subnormal activation against a normal weight, and subnormal times subnormal (exact in fp32: 20 bits)
+    x2 = np.zeros((1, K), np.uint16)
+    x2[0, 3] = 0x0203                   # 515 * 2^-24
+    y2 = lin(x2.view(np.float16), W, None, None)
+    assert (y2[0].astype(np.float64) == 515 * 2.0 ** -24 * want).all()
