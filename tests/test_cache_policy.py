@@ -17,7 +17,7 @@ def run_cache(slots, calls):
     out = []
     try:
         for keys in calls:
-            rc, ptrs, s, h = dz.dz_cache_acquire(c, keys, None, 1024, check=False)
+            rc, ptrs, s, h, _ = dz.dz_cache_acquire(c, keys, None, 1024, check=False)
             if rc != dz.DZ_OK:
                 assert rc == dz.DZ_ERR_ARG
                 out.append(None)
@@ -96,7 +96,7 @@ def test_argument_errors():
         assert dz.dz_cache_acquire(c, [1, 2], None, 1000)[0] == dz.DZ_OK
         # both slots belong to the previous call now: nothing new fits, and nothing changes
         assert dz.dz_cache_acquire(c, [3], None, 1000, check=False)[0] == dz.DZ_ERR_ARG
-        rc, _, slots, hits = dz.dz_cache_acquire(c, [2, 1], None, 1000)
+        rc, _, slots, hits, _ = dz.dz_cache_acquire(c, [2, 1], None, 1000)
         assert hits == [1, 1] and slots == [1, 0]
         assert dz.dz_cache_stats(c) == (2, 2, 0)
     finally:
