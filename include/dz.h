@@ -27,11 +27,15 @@
  *     (codes[n][2g+j] - zero[n][4g/G]) * scale[n][4g/G]   at column 4g + idx[n][2g+j].
  *
  * Shapes the kernels accept: bits in {2,4}; group in {64,128}; N % 16 == 0; K % 256 == 0;
- * 0 <= D <= DZ_MAX_DELTAS; T >= 0 (T == 0 is a no-op).
+ * 0 <= D <= DZ_MAX_DELTAS; T >= 0 (T == 0 is a no-op).  (The format itself only needs K % group == 0
+ * and group % 4 == 0; the kernels stream whole tiles of 16 rows x 256 columns, and every layer shape
+ * of the Llama family is a multiple of that.)
  *
  * Ownership and synchronisation: the caller owns every buffer it passes.  The library owns only
  * the workspace inside dz_ctx (segment tables, split-K partial sums, an error flag), which may grow
- * on a call that needs more than any earlier call (that growth synchronises the stream once).
+ * on a call that needs more than any earlier call (that growth synchronises the stream once; the
+ * buffer it replaces stays allocated until dz_destroy, so a HIP graph recorded before the growth can
+ * still be replayed).
  * A stream that is being captured into a HIP graph can be passed once an eager call with the same
  * shapes has sized the workspace: the calls then record only kernels.  A call that would have to
  * grow the workspace during a capture returns DZ_ERR_HIP and records nothing.
@@ -58,6 +62,7 @@ extern "C" {
 #define DZ_ERR_ALIGN  (-4)  /* a device pointer is not 16-byte aligned                               */
 #define DZ_ERR_HIP    (-5)  /* the HIP runtime reported a failure (text from dz_last_hip_error)      */
 #define DZ_ERR_INDEX  (-6)  /* dz_check: some earlier call saw a request index outside [-1, D)       */
+#define DZ_ERR_LIMIT  (-7)  /* the call needs more workspace than the entry point or context may use */
 
 #define DZ_MAX_DELTAS 128   /* deltas resident for one call                                          */
 #define DZ_MAX_GROUP  4     /* projections in one dz_linear_group call                               */
@@ -72,6 +77,23 @@ const char *dz_last_hip_error(const dz_ctx *ctx);
 /* Create / destroy a context on GPU `device`.  dz_destroy synchronises the device. */
 int dz_create(dz_ctx **ctx, int device);
 int dz_destroy(dz_ctx *ctx);
+
+/*
+ * Per-context options.  The defaults are what the kernels were tuned with; the options exist so that
+ * a test or a sweep can force a particular route through the kernels.  value >= 0; an unknown key or
+ * a value the key does not take returns DZ_ERR_ARG and changes nothing.
+ */
+#define DZ_OPT_SPLIT_K               1  /* k slices per row block (streaming kernel) / per tile (tiled kernels); 0 = chosen per call */
+#define DZ_OPT_WORKGROUPS            2  /* workgroups per launch of the streaming kernel; 0 = eight waves per compute unit            */
+#define DZ_OPT_ROUND_TILES           3  /* k tiles of x a workgroup of the streaming kernel stages at once; 0 = as many as fit        */
+#define DZ_OPT_LARGE_BATCH_STREAMING 4  /* 1 = batches of more than 64 rows also go through the streaming kernel, 64 rows at a time  */
+#define DZ_OPT_WIDE_TILE             5  /* dz_base_gemm on large batches: 0 = never the 256 x 256 tile kernel, 1 = when it has enough
+                                           tiles (default), 2 = always                                                                */
+#define DZ_OPT_REUSE_SEGMENTS        6  /* 1 = the caller promises that a token_to_delta vector passed again at the same address
+                                           with the same T and D is unchanged: consecutive large-batch calls of one layer then share
+                                           one sort.  Setting the option (to either value) forgets the remembered order.             */
+#define DZ_OPT_WG_SHAPE              7  /* streaming kernel workgroup: 0 = chosen per call, 81 / 82 / 42 = waves x row tiles per wave */
+int dz_set_option(dz_ctx *ctx, int key, int value);
 
 /*
  * Size in bytes of one packed delta: the kept values' codes, their 2-bit positions (Section 4.1:
@@ -163,6 +185,19 @@ int dz_linear_group(dz_ctx *ctx, const void *x_f16, int P, const void *const *W_
 int dz_check(dz_ctx *ctx, void *stream);
 
 /*
+ * Measured ceilings of the device, for pricing the kernels (a benchmark prints them beside the
+ * nominal peaks).  Both only enqueue one kernel on `stream`; the caller times it with events.
+ *   dz_probe_read  reads `bytes` (a multiple of 16) of DEVICE memory at buf once, 16 bytes per lane and
+ *                  load, and does nothing else: bytes / time is the read rate HBM sustains.
+ *   dz_probe_mfma  issues iters x 32 dense fp16 matrix instructions per wave on register operands,
+ *                  sixteen waves per compute unit; *flops_out (HOST, may be NULL) receives the floating
+ *                  point operations the launch performs: flops / time is the matrix rate with every
+ *                  memory cost removed.
+ */
+int dz_probe_read(dz_ctx *ctx, const void *buf, size_t bytes, void *stream);
+int dz_probe_mfma(dz_ctx *ctx, int iters, double *flops_out, void *stream);
+
+/*
  * Resident-delta cache: the step before the hot path.  The engine keeps the base model on the GPU
  * and brings compressed deltas in on demand (Section 5.1), a fixed, pre-set number of them per
  * batch at most, moving deltas between GPU memory, host memory and disk as needed (Section 5.4,
@@ -178,27 +213,38 @@ int dz_check(dz_ctx *ctx, void *stream);
  *     host_blobs[i] (HOST memory, `bytes` <= slot_bytes long, pinned if the copy is to overlap with
  *     compute; it must stay valid until the copy has run) is copied into it asynchronously on
  *     copy_stream.
- * Ordering is by events, nothing is synchronised: the copies wait for the work that was enqueued
- * on compute_stream before this call (an evicted delta may still be read by it), and
- * compute_stream waits for the copies, so work enqueued on compute_stream after the call may read
- * every returned address.  Because the slots of the previous call are never evicted, a caller can
- * acquire the deltas of batch i+1 before it enqueues the compute of batch i and have the copies
- * run under that compute.  One cache serves one compute stream.
- * device_blobs_out[n] receives the addresses; slot_out[n] (slot index) and hit_out[n] (1 = was
- * resident) may be NULL.  Keys may repeat within a call (the repeats are hits).  A call with
- * n == 0 does nothing (it does not count as "the previous call" afterwards).
- * Errors: DZ_ERR_ARG for null / negative arguments, bytes > slot_bytes, or more keys to bring in
- * than there are slots outside this and the previous call's (nothing is changed then);
- * DZ_ERR_HIP for runtime failures.
+ * Nothing is synchronised and the compute stream is not touched by dz_cache_acquire: ordering is by
+ * events, through the ticket the call returns.
+ *   dz_cache_wait(cache, ticket, compute_stream)     compute_stream waits for the copies of that
+ *       acquire; call it right before enqueuing the compute that reads the returned addresses.
+ *   dz_cache_release(cache, ticket, compute_stream)  call it right after enqueuing that compute: the
+ *       work enqueued on compute_stream so far was the last reader of that acquire's slots.  A later
+ *       copy that evicts one of them waits for exactly that point and for nothing else.
+ * So a caller acquires the deltas of batch i+1 before it enqueues the compute of batch i (the slots
+ * of the previous acquire are never evicted), and the copies of batch i+1 run while batch i computes:
+ *     t1 = acquire(batch 1)
+ *     for i = 1, 2, ...:  t(i+1) = acquire(batch i+1);  wait(t(i));  compute(batch i);  release(t(i))
+ * A ticket that is never released stays remembered and its slots have no "last reader" event:
+ * evicting one of them drains the whole device first (safe, but it serialises).
+ * device_blobs_out[n] receives the addresses; slot_out[n] (slot index), hit_out[n] (1 = was
+ * resident) and ticket_out may be NULL.  Keys may repeat within a call (the repeats are hits).  A
+ * call with n == 0 does nothing (ticket 0; it does not count as "the previous call" afterwards).
+ * Errors: DZ_ERR_ARG for null / negative arguments, bytes > slot_bytes, an unknown ticket, or more
+ * keys to bring in than there are slots outside this and the previous call's (nothing is changed
+ * then); DZ_ERR_HIP for runtime failures (keys handled before the failure stay resident, the others
+ * keep their old state, addresses from the failing key on come back NULL).
  * dz_cache_create with device < 0 makes a cache without device memory that takes the same
- * decisions and copies nothing (addresses come back NULL): for planning and for tests.
+ * decisions and copies nothing (addresses come back NULL, wait and release do nothing): for
+ * planning and for tests.
  */
 typedef struct dz_cache dz_cache;
 int dz_cache_create(dz_cache **cache, int device, int slots, size_t slot_bytes);
 int dz_cache_destroy(dz_cache *cache);
 int dz_cache_acquire(dz_cache *cache, int n, const int64_t *keys, const void *const *host_blobs,
                      size_t bytes, const void **device_blobs_out, int32_t *slot_out,
-                     int32_t *hit_out, void *copy_stream, void *compute_stream);
+                     int32_t *hit_out, void *copy_stream, int64_t *ticket_out);
+int dz_cache_wait(dz_cache *cache, int64_t ticket, void *compute_stream);
+int dz_cache_release(dz_cache *cache, int64_t ticket, void *compute_stream);
 /* Totals since creation; any pointer may be NULL. */
 int dz_cache_stats(const dz_cache *cache, int64_t *hits, int64_t *misses, int64_t *evictions);
 

@@ -7,20 +7,25 @@ from typing import List, Optional, Sequence
 import torch
 
 __all__ = [
-    "DZ_OK", "DZ_ERR_ARG", "DZ_ERR_SHAPE", "DZ_ERR_BITS", "DZ_ERR_ALIGN", "DZ_ERR_HIP", "DZ_ERR_INDEX",
+    "DZ_OK", "DZ_ERR_ARG", "DZ_ERR_SHAPE", "DZ_ERR_BITS", "DZ_ERR_ALIGN", "DZ_ERR_HIP", "DZ_ERR_INDEX", "DZ_ERR_LIMIT",
+    "DZ_OPT_SPLIT_K", "DZ_OPT_WORKGROUPS", "DZ_OPT_ROUND_TILES", "DZ_OPT_LARGE_BATCH_STREAMING", "DZ_OPT_WIDE_TILE",
+    "DZ_OPT_REUSE_SEGMENTS", "DZ_OPT_WG_SHAPE", "dz_set_option", "dz_probe_read", "dz_probe_mfma",
     "DZ_MAX_DELTAS", "DzError", "lib", "lib_path", "dz_strerror", "dz_create", "dz_destroy",
     "dz_packed_bytes", "dz_pack_delta", "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm",
     "dz_linear", "dz_linear_group", "dz_check", "Context", "SYMBOLS", "DZ_MAX_GROUP",
-    "dz_cache_create", "dz_cache_destroy", "dz_cache_acquire", "dz_cache_stats",
+    "dz_cache_create", "dz_cache_destroy", "dz_cache_acquire", "dz_cache_wait", "dz_cache_release", "dz_cache_stats",
 ]
 
-DZ_OK, DZ_ERR_ARG, DZ_ERR_SHAPE, DZ_ERR_BITS, DZ_ERR_ALIGN, DZ_ERR_HIP, DZ_ERR_INDEX = 0, -1, -2, -3, -4, -5, -6
+DZ_OK, DZ_ERR_ARG, DZ_ERR_SHAPE, DZ_ERR_BITS, DZ_ERR_ALIGN, DZ_ERR_HIP, DZ_ERR_INDEX, DZ_ERR_LIMIT = 0, -1, -2, -3, -4, -5, -6, -7
+(DZ_OPT_SPLIT_K, DZ_OPT_WORKGROUPS, DZ_OPT_ROUND_TILES, DZ_OPT_LARGE_BATCH_STREAMING, DZ_OPT_WIDE_TILE,
+ DZ_OPT_REUSE_SEGMENTS, DZ_OPT_WG_SHAPE) = 1, 2, 3, 4, 5, 6, 7
 DZ_MAX_DELTAS = 128
 DZ_MAX_GROUP = 4
 
-SYMBOLS = ["dz_strerror", "dz_last_hip_error", "dz_create", "dz_destroy", "dz_packed_bytes", "dz_pack_delta",
+SYMBOLS = ["dz_strerror", "dz_last_hip_error", "dz_create", "dz_destroy", "dz_set_option", "dz_probe_read", "dz_probe_mfma", "dz_packed_bytes", "dz_pack_delta",
            "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm", "dz_linear", "dz_linear_group", "dz_check",
-           "dz_cache_create", "dz_cache_destroy", "dz_cache_acquire", "dz_cache_stats"]
+           "dz_cache_create", "dz_cache_destroy", "dz_cache_acquire", "dz_cache_wait", "dz_cache_release",
+           "dz_cache_stats"]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _lib = None
@@ -63,11 +68,16 @@ def lib() -> ctypes.CDLL:
         L.dz_linear_group.argtypes = [vp, vp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, ctypes.POINTER(vp),
                                       ctypes.POINTER(ci), ci, ci, ci, ci, vp]
         L.dz_check.argtypes = [vp, vp]
+        L.dz_set_option.argtypes = [vp, ci, ci]
+        L.dz_probe_read.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.dz_probe_mfma.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double), vp]
         i64p, i32p = ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32)
         L.dz_cache_create.argtypes = [ctypes.POINTER(vp), ci, ci, ctypes.c_size_t]
         L.dz_cache_destroy.argtypes = [vp]
         L.dz_cache_acquire.argtypes = [vp, ci, i64p, ctypes.POINTER(vp), ctypes.c_size_t, ctypes.POINTER(vp), i32p, i32p,
-                                       vp, vp]
+                                       vp, i64p]
+        L.dz_cache_wait.argtypes = [vp, ctypes.c_int64, vp]
+        L.dz_cache_release.argtypes = [vp, ctypes.c_int64, vp]
         L.dz_cache_stats.argtypes = [vp, i64p, i64p, i64p]
         for name in SYMBOLS:
             getattr(L, name)
@@ -116,6 +126,21 @@ def dz_create(device: int = 0) -> int:
 
 def dz_destroy(ctx: int) -> int:
     return lib().dz_destroy(ctx)
+
+
+def dz_set_option(ctx, key: int, value: int, check=True) -> int:
+    return _raise(ctx, lib().dz_set_option(ctx, int(key), int(value)), "dz_set_option", check)
+
+
+def dz_probe_read(ctx, buf, nbytes: int, stream=None, check=True) -> int:
+    return _raise(ctx, lib().dz_probe_read(ctx, _ptr(buf), int(nbytes), _stream(stream)), "dz_probe_read", check)
+
+
+def dz_probe_mfma(ctx, iters: int, stream=None):
+    """Returns the floating point operations the launch performs."""
+    flops = ctypes.c_double()
+    _raise(ctx, lib().dz_probe_mfma(ctx, int(iters), ctypes.byref(flops), _stream(stream)), "dz_probe_mfma", True)
+    return float(flops.value)
 
 
 def dz_packed_bytes(N: int, K: int, bits: int, group: int) -> int:
@@ -202,9 +227,10 @@ def dz_cache_destroy(cache: int) -> int:
 
 
 def dz_cache_acquire(cache, keys: Sequence[int], host_blobs: Optional[Sequence[Optional[torch.Tensor]]], nbytes: int,
-                     copy_stream=None, compute_stream=None, check=True):
-    """Returns (rc, device addresses, slots, hits).  host_blobs: host tensors (pinned for overlap), one per key;
-    None for a cache created with device < 0.  Streams: torch streams or raw handles; None = the current stream."""
+                     copy_stream=None, check=True):
+    """Returns (rc, device addresses, slots, hits, ticket).  host_blobs: host tensors (pinned for overlap), one per
+    key; None for a cache created with device < 0.  copy_stream: a torch stream or raw handle; None = the current
+    stream."""
     n = len(keys)
     karr = (ctypes.c_int64 * max(n, 1))(*[int(k) for k in keys])
     harr = (ctypes.c_void_p * max(n, 1))()
@@ -219,13 +245,27 @@ def dz_cache_acquire(cache, keys: Sequence[int], host_blobs: Optional[Sequence[O
     darr = (ctypes.c_void_p * max(n, 1))()
     sarr = (ctypes.c_int32 * max(n, 1))()
     hitarr = (ctypes.c_int32 * max(n, 1))()
-    use_streams = host_blobs is not None
+    ticket = ctypes.c_int64()
     rc = lib().dz_cache_acquire(cache, n, karr, harr if host_blobs is not None else None, int(nbytes), darr, sarr, hitarr,
-                                _stream(copy_stream) if use_streams else None,
-                                _stream(compute_stream) if use_streams else None)
+                                _stream(copy_stream) if host_blobs is not None else None, ctypes.byref(ticket))
     if rc != DZ_OK and check:
         raise DzError(rc, "dz_cache_acquire")
-    return rc, [int(darr[i] or 0) for i in range(n)], [int(sarr[i]) for i in range(n)], [int(hitarr[i]) for i in range(n)]
+    return (rc, [int(darr[i] or 0) for i in range(n)], [int(sarr[i]) for i in range(n)],
+            [int(hitarr[i]) for i in range(n)], int(ticket.value))
+
+
+def dz_cache_wait(cache, ticket: int, compute_stream=None) -> int:
+    rc = lib().dz_cache_wait(cache, int(ticket), _stream(compute_stream))
+    if rc != DZ_OK:
+        raise DzError(rc, "dz_cache_wait")
+    return rc
+
+
+def dz_cache_release(cache, ticket: int, compute_stream=None) -> int:
+    rc = lib().dz_cache_release(cache, int(ticket), _stream(compute_stream))
+    if rc != DZ_OK:
+        raise DzError(rc, "dz_cache_release")
+    return rc
 
 
 def dz_cache_stats(cache):
@@ -241,6 +281,9 @@ class Context:
 
     def __init__(self, device: int = 0):
         self.h = dz_create(device)
+
+    def set_option(self, key: int, value: int) -> int:
+        return dz_set_option(self.h, key, value)
 
     def close(self):
         if self.h:

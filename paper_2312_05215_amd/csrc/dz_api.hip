@@ -20,13 +20,6 @@ int check_shape(int N, int K, int bits, int group, bool need_fmt)
     return DZ_OK;
 }
 
-int env_int(const char *name, int dflt)
-{
-    const char *s = getenv(name);
-    if (!s || !*s) return dflt;
-    return atoi(s);
-}
-
 struct DeviceGuard {
     int prev = -1;
     bool ok = false;
@@ -63,16 +56,26 @@ static int quiesce_for_growth(dz_ctx *ctx, hipStream_t st)
     return dz_set_hip_error(ctx, e);
 }
 
+// A buffer that a growth replaces is kept until dz_destroy: the kernel nodes of a HIP graph recorded
+// earlier still hold its address, and a replay must find it allocated.
+static int retire(dz_ctx *ctx, void *p)
+{
+    if (!p) return DZ_OK;
+    if (ctx->n_retired >= (int)(sizeof(ctx->retired) / sizeof(ctx->retired[0]))) return DZ_ERR_LIMIT;
+    ctx->retired[ctx->n_retired++] = p;
+    return DZ_OK;
+}
+
 int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st)
 {
     if (bytes <= ctx->partial_bytes) return DZ_OK;
+    if (ctx->static_ws) return DZ_ERR_LIMIT;
     if (int rc = quiesce_for_growth(ctx, st)) return rc;
-    hipError_t e;
-    if (ctx->partial) (void)hipFree(ctx->partial);
+    if (int rc = retire(ctx, ctx->partial)) return rc;
     ctx->partial = nullptr;
     ctx->partial_bytes = 0;
     size_t want = bytes + bytes / 4;
-    e = hipMalloc((void **)&ctx->partial, want);
+    hipError_t e = hipMalloc((void **)&ctx->partial, want);
     if (e != hipSuccess) return dz_set_hip_error(ctx, e);
     ctx->partial_bytes = want;
     return DZ_OK;
@@ -81,13 +84,13 @@ int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st)
 int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st)
 {
     if (n <= ctx->counters_cap) return DZ_OK;
+    if (ctx->static_ws) return DZ_ERR_LIMIT;
     if (int rc = quiesce_for_growth(ctx, st)) return rc;
-    hipError_t e;
-    if (ctx->counters) (void)hipFree(ctx->counters);
+    if (int rc = retire(ctx, ctx->counters)) return rc;
     ctx->counters = nullptr;
     ctx->counters_cap = 0;
     int want = n * 2;
-    e = hipMalloc((void **)&ctx->counters, (size_t)want * 4);
+    hipError_t e = hipMalloc((void **)&ctx->counters, (size_t)want * 4);
     if (e != hipSuccess) return dz_set_hip_error(ctx, e);
     e = hipMemset(ctx->counters, 0, (size_t)want * 4);
     if (e != hipSuccess) return dz_set_hip_error(ctx, e);
@@ -95,22 +98,48 @@ int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st)
     return DZ_OK;
 }
 
+int dz_ensure_lora(dz_ctx *ctx, size_t bytes, hipStream_t st)
+{
+    if (bytes <= ctx->lora_u_bytes) return DZ_OK;
+    if (ctx->static_ws) return DZ_ERR_LIMIT;
+    if (int rc = quiesce_for_growth(ctx, st)) return rc;
+    if (int rc = retire(ctx, ctx->lora_u)) return rc;
+    ctx->lora_u = nullptr;
+    ctx->lora_u_bytes = 0;
+    size_t want = bytes + bytes / 4;
+    hipError_t e = hipMalloc((void **)&ctx->lora_u, want);
+    if (e != hipSuccess) return dz_set_hip_error(ctx, e);
+    ctx->lora_u_bytes = want;
+    return DZ_OK;
+}
+
 static int ensure_seg(dz_ctx *ctx, int T, hipStream_t st)
 {
     if (T <= ctx->seg_cap) return DZ_OK;
+    if (ctx->static_ws) return DZ_ERR_LIMIT;
     if (int rc = quiesce_for_growth(ctx, st)) return rc;
-    hipError_t e;
-    if (ctx->seg_perm) (void)hipFree(ctx->seg_perm);
-    if (ctx->seg_key) (void)hipFree(ctx->seg_key);
+    if (int rc = retire(ctx, ctx->seg_perm)) return rc;
+    if (int rc = retire(ctx, ctx->seg_key)) return rc;
     ctx->seg_perm = ctx->seg_key = nullptr;
     ctx->seg_cap = 0;
+    ctx->seg_ids = nullptr;
     int want = T * 2;
-    e = hipMalloc((void **)&ctx->seg_perm, (size_t)want * 4);
+    hipError_t e = hipMalloc((void **)&ctx->seg_perm, (size_t)want * 4);
     if (e != hipSuccess) return dz_set_hip_error(ctx, e);
     e = hipMalloc((void **)&ctx->seg_key, (size_t)want * 4);
     if (e != hipSuccess) return dz_set_hip_error(ctx, e);
     ctx->seg_cap = want;
     return DZ_OK;
+}
+
+// The entry point that allocates nothing keeps a sticky error word of its own per GPU; dz_check
+// reports it too when that translation unit is part of the library.
+extern "C" int32_t *dz_static_err_word(int device) __attribute__((weak));
+
+__global__ void dz_clear_words_kernel(int32_t *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 extern "C" {
@@ -125,6 +154,7 @@ const char *dz_strerror(int rc)
     case DZ_ERR_ALIGN: return "device pointer is not 16-byte aligned";
     case DZ_ERR_HIP: return "HIP runtime failure";
     case DZ_ERR_INDEX: return "a request index was outside [-1, D)";
+    case DZ_ERR_LIMIT: return "the call needs more workspace than this entry point or context may use";
     default: return "unknown error";
     }
 }
@@ -139,22 +169,14 @@ int dz_create(dz_ctx **out, int device)
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return DZ_ERR_ARG;
     dz_ctx *ctx = new (std::nothrow) dz_ctx();
     if (!ctx) return DZ_ERR_ARG;
-    memset(ctx, 0, sizeof(*ctx));
     ctx->device = device;
-    ctx->force_splits = env_int("DZ_SPLITS", 0);
-    ctx->target_wgs = env_int("DZ_TARGET_WGS", 0);       // 0: eight waves per CU
-    if (ctx->target_wgs < 0) ctx->target_wgs = 0;
-    ctx->wg_waves = env_int("DZ_WAVES", 0);
-    ctx->wg_rtiles = env_int("DZ_RTILES", 0);
-    ctx->round_tiles = env_int("DZ_ROUND_TILES", 0);
-    ctx->no_prefill = env_int("DZ_NO_PREFILL", 0);
-    ctx->tile_kernel = env_int("DZ_TILE", 1);
     DeviceGuard guard(device);
     hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
     if (e == hipSuccess) {
         int n = 0;
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess) ctx->num_cus = n;
     }
+    if (e == hipSuccess && dz_static_err_word) (void)dz_static_err_word(device);   // set-up of the static workspace on this GPU
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->err_flag, 4);
     if (e == hipSuccess) e = hipMemset(ctx->err_flag, 0, 4);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->seg_counts, (size_t)(DZ_SEG_MAX_D + 1) * 4);
@@ -194,6 +216,8 @@ int dz_destroy(dz_ctx *ctx)
         if (ctx->seg_key) (void)hipFree(ctx->seg_key);
         if (ctx->counters) (void)hipFree(ctx->counters);
         if (ctx->partial) (void)hipFree(ctx->partial);
+        if (ctx->lora_u) (void)hipFree(ctx->lora_u);
+        for (int i = 0; i < ctx->n_retired; ++i) (void)hipFree(ctx->retired[i]);
     }
     delete ctx;
     return DZ_OK;
@@ -283,8 +307,14 @@ static int run_group(dz_ctx *ctx, const void *x, int P, const void *const *W, co
     } else if (has_delta && D > 0) {
         int rc = ensure_seg(ctx, T, st);
         if (rc) return rc;
-        rc = dz_launch_segment(ctx, ids, T, D, nullptr, nullptr, ctx->seg_perm, ctx->seg_key, st);
-        if (rc) return rc;
+        // With DZ_OPT_REUSE_SEGMENTS the caller promises that an index vector at the same address with
+        // the same T and D still holds the same values: the projections of one layer then share one sort.
+        const bool same = ctx->reuse_segments && ctx->seg_ids == ids && ctx->seg_T == T && ctx->seg_D == D;
+        if (!same) {
+            rc = dz_launch_segment(ctx, ids, T, D, nullptr, nullptr, ctx->seg_perm, ctx->seg_key, st);
+            if (rc) return rc;
+            ctx->seg_ids = ids; ctx->seg_T = T; ctx->seg_D = D;
+        }
         a.perm = ctx->seg_perm;
         a.key = ctx->seg_key;
     }
@@ -317,7 +347,7 @@ static int run_group(dz_ctx *ctx, const void *x, int P, const void *const *W, co
     return DZ_OK;
 }
 
-static int run_linear(dz_ctx *ctx, const void *x, const void *W, const void *const *deltas, int D,
+int dz_run_linear(dz_ctx *ctx, const void *x, const void *W, const void *const *deltas, int D,
                       const int32_t *ids, void *out, int T, int N, int K, int bits, int group, int accumulate,
                       bool has_base, bool has_delta, hipStream_t st)
 {
@@ -326,20 +356,20 @@ static int run_linear(dz_ctx *ctx, const void *x, const void *W, const void *con
 
 int dz_base_gemm(dz_ctx *ctx, const void *x, const void *W, void *out, int T, int N, int K, void *stream)
 {
-    return run_linear(ctx, x, W, nullptr, 0, nullptr, out, T, N, K, 4, 128, 0, true, false, (hipStream_t)stream);
+    return dz_run_linear(ctx, x, W, nullptr, 0, nullptr, out, T, N, K, 4, 128, 0, true, false, (hipStream_t)stream);
 }
 
 int dz_sbmm(dz_ctx *ctx, const void *x, const void *const *deltas, int D, const int32_t *ids, void *out, int T,
             int N, int K, int bits, int group, int accumulate, void *stream)
 {
-    return run_linear(ctx, x, nullptr, deltas, D, ids, out, T, N, K, bits, group, accumulate ? 1 : 0, false, true,
+    return dz_run_linear(ctx, x, nullptr, deltas, D, ids, out, T, N, K, bits, group, accumulate ? 1 : 0, false, true,
                       (hipStream_t)stream);
 }
 
 int dz_linear(dz_ctx *ctx, const void *x, const void *W, const void *const *deltas, int D, const int32_t *ids,
               void *out, int T, int N, int K, int bits, int group, void *stream)
 {
-    return run_linear(ctx, x, W, deltas, D, ids, out, T, N, K, bits, group, 0, true, true, (hipStream_t)stream);
+    return dz_run_linear(ctx, x, W, deltas, D, ids, out, T, N, K, bits, group, 0, true, true, (hipStream_t)stream);
 }
 
 int dz_linear_group(dz_ctx *ctx, const void *x, int P, const void *const *W, const void *const *deltas, int D,
@@ -354,17 +384,53 @@ int dz_check(dz_ctx *ctx, void *stream)
     if (!ctx) return DZ_ERR_ARG;
     DeviceGuard guard(ctx->device);
     hipStream_t st = (hipStream_t)stream;
-    int32_t flag = 0;
-    hipError_t e = hipMemcpyAsync(&flag, ctx->err_flag, 4, hipMemcpyDeviceToHost, st);
+    // the context's own error word, and the one dz_linear_static keeps in the static workspace of this GPU
+    int32_t *words[2] = {ctx->err_flag, nullptr};
+    if (dz_static_err_word) words[1] = dz_static_err_word(ctx->device);
+    int32_t flag[2] = {0, 0};
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < 2 && e == hipSuccess; ++i)
+        if (words[i]) e = hipMemcpyAsync(&flag[i], words[i], 4, hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) return dz_set_hip_error(ctx, e);
-    if (flag) {
-        e = hipMemsetAsync(ctx->err_flag, 0, 4, st);
+    if (flag[0] | flag[1]) {
+        for (int i = 0; i < 2 && e == hipSuccess; ++i)
+            if (words[i] && flag[i]) {
+                hipLaunchKernelGGL(dz_clear_words_kernel, dim3(1), dim3(64), 0, st, words[i], 1);
+                e = hipGetLastError();
+            }
         if (e == hipSuccess) e = hipStreamSynchronize(st);
         if (e != hipSuccess) return dz_set_hip_error(ctx, e);
         return DZ_ERR_INDEX;
     }
     return DZ_OK;
+}
+
+int dz_set_option(dz_ctx *ctx, int key, int value)
+{
+    if (!ctx || value < 0) return DZ_ERR_ARG;
+    switch (key) {
+    case DZ_OPT_SPLIT_K: ctx->force_splits = value; return DZ_OK;
+    case DZ_OPT_WORKGROUPS: ctx->target_wgs = value; return DZ_OK;
+    case DZ_OPT_ROUND_TILES: ctx->round_tiles = value; return DZ_OK;
+    case DZ_OPT_LARGE_BATCH_STREAMING: ctx->no_prefill = value ? 1 : 0; return DZ_OK;
+    case DZ_OPT_WIDE_TILE:
+        if (value > 2) return DZ_ERR_ARG;
+        ctx->tile_kernel = value;
+        return DZ_OK;
+    case DZ_OPT_REUSE_SEGMENTS:
+        ctx->reuse_segments = value ? 1 : 0;
+        ctx->seg_ids = nullptr;
+        return DZ_OK;
+    case DZ_OPT_WG_SHAPE:
+        // waves x row tiles per wave of the streaming kernel: only the shapes that are built
+        if (value == 0) { ctx->wg_waves = ctx->wg_rtiles = 0; return DZ_OK; }
+        if (value != 81 && value != 82 && value != 42) return DZ_ERR_ARG;
+        ctx->wg_waves = value / 10;
+        ctx->wg_rtiles = value % 10;
+        return DZ_OK;
+    default: return DZ_ERR_ARG;
+    }
 }
 
 }  // extern "C"

@@ -7,28 +7,38 @@
 #include "dz_layout.h"
 
 struct dz_ctx {
-    int device;
+    int device = 0;
     // workspace (device memory owned by the context)
-    int32_t *seg_perm;      // [seg_cap] request indices in delta-sorted order
-    int32_t *seg_key;       // [seg_cap] delta index of each sorted position (D = none)
-    int32_t *seg_counts;    // [DZ_SEG_MAX_D + 1]
-    int32_t *seg_offsets;   // [DZ_SEG_MAX_D + 2]
-    int seg_cap;
-    float *partial;         // split-K partial sums
-    size_t partial_bytes;
-    int32_t *counters;      // arrival counters, one per (chunk, row block); all zero between calls
-    int counters_cap;
-    int32_t *err_flag;      // sticky device-side error word
-    char hip_err[256];
-    // tuning knobs (environment overrides, read once)
-    int force_splits;       // DZ_SPLITS
-    int target_wgs;         // DZ_TARGET_WGS
-    int round_tiles;        // DZ_ROUND_TILES
-    int no_prefill;         // DZ_NO_PREFILL: serve large batches with the streaming kernel (chunks of 64 rows)
-    int wg_waves, wg_rtiles; // DZ_WAVES, DZ_RTILES: workgroup shape of the streaming kernel
-    int num_cus;            // compute units of the device
-    int tile_kernel;        // DZ_TILE: 1 (default) = the base product of large batches goes to the 256 x 256 tile
-                            // kernel when it has enough tiles, 2 = always, 0 = never
+    int32_t *seg_perm = nullptr;    // [seg_cap] request indices in delta-sorted order
+    int32_t *seg_key = nullptr;     // [seg_cap] delta index of each sorted position (D = none)
+    int32_t *seg_counts = nullptr;  // [DZ_SEG_MAX_D + 1]
+    int32_t *seg_offsets = nullptr; // [DZ_SEG_MAX_D + 2]
+    int seg_cap = 0;
+    float *partial = nullptr;       // split-K partial sums
+    size_t partial_bytes = 0;
+    int32_t *counters = nullptr;    // arrival counters, one per (chunk, row block); all zero between calls
+    int counters_cap = 0;
+    int32_t *err_flag = nullptr;    // sticky device-side error word
+    float *lora_u = nullptr;        // low-rank SBMM: x . A^T of every request, fp32 [T][rank]
+    size_t lora_u_bytes = 0;
+    // Buffers a growth replaced.  A HIP graph recorded earlier may still hold their addresses in its
+    // kernel nodes, so they stay allocated until dz_destroy.
+    void *retired[64] = {};
+    int n_retired = 0;
+    bool static_ws = false;         // the workspace is the library's static device array: it never grows
+    char hip_err[256] = {};
+    // options (dz_set_option)
+    int force_splits = 0;           // DZ_OPT_SPLIT_K
+    int target_wgs = 0;             // DZ_OPT_WORKGROUPS
+    int round_tiles = 0;            // DZ_OPT_ROUND_TILES
+    int no_prefill = 0;             // DZ_OPT_LARGE_BATCH_STREAMING
+    int wg_waves = 0, wg_rtiles = 0; // DZ_OPT_WG_SHAPE: workgroup shape of the streaming kernel
+    int num_cus = 0;                // compute units of the device
+    int tile_kernel = 1;            // DZ_OPT_WIDE_TILE
+    int reuse_segments = 0;         // DZ_OPT_REUSE_SEGMENTS
+    // the request order the last segment pass left in seg_perm / seg_key
+    const int32_t *seg_ids = nullptr;
+    int seg_T = -1, seg_D = -1;
 };
 
 #define DZ_SEG_MAX_D 8192
@@ -69,6 +79,13 @@ struct DzStreamArgs {
 };
 
 int dz_set_hip_error(dz_ctx *ctx, hipError_t e);
+// one projection through the same dispatch as the public entry points (which are thin wrappers of it)
+extern "C" int dz_run_linear(dz_ctx *ctx, const void *x, const void *W, const void *const *deltas, int D,
+                             const int32_t *ids, void *out, int T, int N, int K, int bits, int group, int accumulate,
+                             bool has_base, bool has_delta, hipStream_t st);
+int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st);
+int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
+int dz_ensure_lora(dz_ctx *ctx, size_t bytes, hipStream_t st);
 
 // A kernel may use more than 64 KB of dynamic LDS only after an attribute has been set for it, once
 // per device.  `done` (one static word per kernel instantiation) remembers the devices it has been

@@ -30,8 +30,6 @@
 // moves 192 KB per 256 k), not by the MFMA pipes.
 #include "dz_mma.h"
 
-int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st);
-int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
 
 namespace {
 
@@ -327,14 +325,11 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     ci.kt = kb; ci.seg = 0;
     const int ndelta = nseg * (ke - kb);  // delta tiles this workgroup multiplies
     int ti = 0;
-#ifndef PF_ILV
-#define PF_ILV 1
-#endif
     // Fused launches multiply the delta tiles between the base steps of their k tile -- segment sg
     // after step sg % 4 -- so that the W and x loads each step sends out keep flowing during the
     // delta work; the W ring is then two buffers deep (one step ahead), which leaves the registers
     // for it.  Base-only launches prefetch W three steps ahead.
-    constexpr bool ILV = HAS_BASE && HAS_DELTA && PF_ILV;
+    constexpr bool ILV = HAS_BASE && HAS_DELTA;
     constexpr int DIST = ILV ? 1 : 3;          // W prefetch distance in steps
     if constexpr (HAS_BASE) {
         base_issue<PR>(rw, wrow, lo.w, 4 * kb, bwA);

@@ -592,8 +592,6 @@ hipError_t launch_kind(const DzStreamArgs &a, int J, const DzGroup &gp, const Dz
 }  // namespace
 
 // Host side: choose the decomposition, make sure the workspace is large enough, launch.
-int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st);
-int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
 
 int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group, const DzGroupPtrs &dp, hipStream_t st)
 {

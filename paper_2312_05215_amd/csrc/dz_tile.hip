@@ -22,8 +22,6 @@
 // packed-delta operands of a wave no longer fit beside them.
 #include "dz_mma.h"
 
-int dz_ensure_partial(dz_ctx *ctx, size_t bytes, hipStream_t st);
-int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st);
 
 namespace {
 

@@ -1,4 +1,9 @@
-"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+"""GPU parity at the full sizes of the five workloads.
+
+bench.py issues q,k,v as one dz_linear_group call, gate,up as another, and o and down as dz_linear
+calls.  test_fullsize_grouped_launches makes exactly those grouped calls (same generator keys, the
+first projection's x for the group, same entry point) for every workload; test_fullsize_sampled_rows
+covers every projection shape through dz_linear, which is also how bench.py issues o and down.
 
 Inputs are generated on the GPU with the seeded generator; the oracle cannot redo a whole layer
 in seconds, so it recomputes a sample of output features (rows of W and of every delta, chosen to
@@ -84,3 +89,100 @@ def test_fullsize_base_product_of_the_prefill_batch(dz, N, K):
         ref = oracle.c.linear(x.cpu().numpy(), W[ridx].cpu().numpy(), None, None)
         max_rel, mean_abs = assert_close(out[:, ridx], ref, f"base {N}x{K}")
         print(f"  max_rel={max_rel:.2e} mean_abs={mean_abs:.2e}", flush=True)
+
+
+def _oracle_rows(cfg, p, x, ids, rows):
+    """Oracle outputs of the sampled output features `rows` of projection p for all requests."""
+    ridx = torch.as_tensor(rows, device="cuda")
+    Wn = p.W[ridx].cpu().numpy()
+    dense = []
+    for t in p.tabs:
+        s = t.rows(ridx).to("cpu")
+        assert oracle.c.validate(s.codes.numpy(), s.idx.numpy(), s.scale.numpy(), s.zero.numpy(), cfg.bits, cfg.group) == 0
+        dense.append(oracle.c.dequant(s.codes.numpy(), s.idx.numpy(), s.scale.numpy(), s.zero.numpy(), cfg.bits, cfg.group))
+    return ridx, oracle.c.linear(x.cpu().numpy(), Wn, dense, ids.numpy())
+
+
+def _grouped_cases():
+    out = []
+    for name in ("7b_decode", "7b_decode_many", "70b_stack", "13b_prefill"):
+        cfg = S.config(name)
+        projs = S.projections_of(cfg)
+        for g in S.launch_groups(cfg):
+            if len(g) > 1:
+                out.append((name, tuple(g), "+".join(str(projs[i][1]) for i in g) + f"x{projs[g[0]][2]}"))
+    return out
+
+
+GROUPED = _grouped_cases()
+
+
+@pytest.mark.parametrize("cfgname,gidx,label", GROUPED, ids=[f"{c}-{l}" for c, _, l in GROUPED])
+def test_fullsize_grouped_launches(dz, cfgname, gidx, label):
+    """The launches bench.py times: one dz_linear_group call over the projections that share x, at
+    full size, with the workgroup ranges crossing row-block and projection boundaries and split-k
+    partial sums meeting; every projection's sampled output features against the oracle."""
+    print(f"grouped {cfgname} {label}", flush=True)
+    cfg = S.config(cfgname)
+    projs = S.projections_of(cfg)
+    ids = cfg.make_ids(S.stream(0, cfg.name, "ids"))
+    d_ids = ids.cuda()
+    with dz.Context(0) as c:
+        sel = []
+        for i in gidx:
+            name, N, K = projs[i]
+            p = S.make_projection(cfg, 0, 0, name, N, K, device="cuda")
+            nbytes = dz.dz_packed_bytes(N, K, cfg.bits, cfg.group)
+            packed = []
+            for t in p.tabs:
+                buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+                dz.dz_pack_delta(c.h, t.codes, t.idx, t.scale, t.zero, N, K, cfg.bits, cfg.group, buf)
+                packed.append(buf)
+            sel.append((p, packed, torch.full((cfg.T, N), 7.0, dtype=torch.float16, device="cuda")))
+        x = sel[0][0].x                       # bench.py: the first projection's x stands for the shared input
+        K = sel[0][0].K
+        dz.dz_linear_group(c.h, x, [p.W for p, _, _ in sel], [pk for _, pk, _ in sel], d_ids, [o for _, _, o in sel],
+                           cfg.T, [p.N for p, _, _ in sel], K, cfg.bits, cfg.group)
+        assert dz.dz_check(c.h) == dz.DZ_OK
+        for j, (p, _, o) in enumerate(sel):
+            assert torch.isfinite(o.float()).all()
+            ridx, ref = _oracle_rows(cfg, p, x, ids, _sample_rows(p.N, seed=j))
+            max_rel, mean_abs = assert_close(o[:, ridx], ref, f"{cfgname} {label} projection {j}")
+            print(f"  projection {j} ({p.N}x{K}): max_rel={max_rel:.2e} mean_abs={mean_abs:.2e}", flush=True)
+            ref_base = oracle.c.linear(x.cpu().numpy(), p.W[ridx].cpu().numpy(), None, None)
+            assert np.abs(ref - ref_base).max() > 10 * np.abs(o[:, ridx].float().cpu().numpy() - ref).max()
+
+
+def test_grouped_split_k_launch_is_reproducible(dz):
+    """Split-k partial sums meet in a fixed order, whoever arrives last: fifty repeats of one grouped
+    full-size launch give the same bits every time."""
+    cfg = S.config("7b_decode")
+    projs = S.projections_of(cfg)
+    gidx = S.launch_groups(cfg)[0]
+    ids = cfg.make_ids(S.stream(0, cfg.name, "ids")).cuda()
+    with dz.Context(0) as c:
+        Ws, packs, Ns = [], [], []
+        x = None
+        for i in gidx:
+            name, N, K = projs[i]
+            p = S.make_projection(cfg, 0, 0, name, N, K, device="cuda")
+            nbytes = dz.dz_packed_bytes(N, K, cfg.bits, cfg.group)
+            packed = []
+            for t in p.tabs:
+                buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+                dz.dz_pack_delta(c.h, t.codes, t.idx, t.scale, t.zero, N, K, cfg.bits, cfg.group, buf)
+                packed.append(buf)
+            Ws.append(p.W); packs.append(packed); Ns.append(N)
+            x = p.x if x is None else x
+            del p
+        first = None
+        for rep in range(50):
+            outs = [torch.full((cfg.T, N), 7.0, dtype=torch.float16, device="cuda") for N in Ns]
+            dz.dz_linear_group(c.h, x, Ws, packs, ids, outs, cfg.T, Ns, projs[gidx[0]][2], cfg.bits, cfg.group)
+            torch.cuda.synchronize()
+            if first is None:
+                first = outs
+                continue
+            for a, b in zip(first, outs):
+                assert torch.equal(a, b), f"repeat {rep} differs"
+        assert dz.dz_check(c.h) == dz.DZ_OK

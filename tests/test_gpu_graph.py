@@ -88,3 +88,39 @@ def test_growth_during_capture_is_an_error(dz):
         dz.dz_linear(c.h, big.dx, big.dW, big.packed, big.dids, ob, 5000, 32, 256, 4, 64)
         assert dz.dz_check(c.h) == dz.DZ_OK
         assert_close(ob, big.y, "after failed capture")
+
+
+def test_replay_after_the_workspace_grew(dz):
+    """A graph recorded before the workspace grows still replays correctly afterwards: the buffers a
+    growth replaces stay allocated until dz_destroy (the graph's kernel nodes hold their addresses)."""
+    import oracle
+    with dz.Context(0) as c:
+        c.set_option(dz.DZ_OPT_SPLIT_K, 3)               # split k: the launch uses partial sums and counters
+        small = Case(dz, c.h, 52, 32, 96, 1536, 4, 4, 128, "uniform")
+        o = small.out(fill=7.0)
+        dz.dz_linear(c.h, small.dx, small.dW, small.packed, small.dids, o, 32, 96, 1536, 4, 128)
+        torch.cuda.synchronize()
+        assert_close(o, small.y, "eager")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            dz.dz_linear(c.h, small.dx, small.dW, small.packed, small.dids, o, 32, 96, 1536, 4, 128)
+        # an eager call whose partial sums exceed the initial workspace (8 slices x 64 x 20480 x 4 bytes = 40 MiB)
+        c.set_option(dz.DZ_OPT_SPLIT_K, 8)
+        T, N, K = 64, 20480, 2048
+        W = S.make_base(N, K, S.stream(53, "W"), 0.02).cuda()
+        x = S.make_x(T, K, S.stream(53, "x")).cuda()
+        big = torch.empty(T, N, dtype=torch.float16, device="cuda")
+        print("growing the workspace", flush=True)
+        dz.dz_base_gemm(c.h, x, W, big, T, N, K)
+        assert dz.dz_check(c.h) == dz.DZ_OK
+        rows = torch.arange(0, N, 997, device="cuda")
+        assert_close(big[:, rows], oracle.c.linear(x.cpu().numpy(), W[rows].cpu().numpy(), None, None), "big base")
+        for rep in range(2):
+            xn = S.make_x(32, 1536, S.stream(54 + rep, "x"))
+            small.dx.copy_(xn)
+            o.fill_(7.0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert dz.dz_check(c.h) == dz.DZ_OK
+            assert_close(o, oracle.c.linear(xn.numpy(), small.W.numpy(), small.dense, small.ids.numpy()), f"replay {rep} after growth")

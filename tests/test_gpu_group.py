@@ -1,8 +1,6 @@
 """GPU parity: dz_linear_group -- several projections that share x and the request indices, one
 call -- against the CPU oracle, projection by projection (each is the linear layer of paper
 Section 5.1 Eq. (2); stacking them along the output dimension changes no result)."""
-import os
-
 import pytest
 import torch
 
@@ -39,28 +37,23 @@ def _oracle(cs, x, ids):
 def test_group_matches_oracle(dz, group, splits):
     name, T, K, D, bits, G, ids, Ns = group
     print(f"group {name} splits={splits}", flush=True)
-    if splits == "auto":
-        os.environ.pop("DZ_SPLITS", None)
-    else:
-        os.environ["DZ_SPLITS"] = splits
-    try:
-        with dz.Context(0) as c:
-            cases = _make(dz, c, group)
-            x, idv = cases[0].x, cases[0].ids
-            outs = [cs.out(fill=7.0) for cs in cases]
-            dz.dz_linear_group(c.h, cases[0].dx, [cs.dW for cs in cases], [cs.packed for cs in cases], cases[0].dids,
-                               outs, T, Ns, K, bits, G)
-            assert dz.dz_check(c.h) == dz.DZ_OK
-            for p, cs in enumerate(cases):
-                ref = _oracle(cs, x, idv)
-                assert_close(outs[p], ref, f"{name} projection {p}")
-                # and the single-projection entry point agrees to within the same bar
-                o1 = cs.out(fill=7.0)
-                dz.dz_linear(c.h, cases[0].dx, cs.dW, cs.packed, cases[0].dids, o1, T, cs.N, K, bits, G)
-                assert_close(o1, ref, f"{name} projection {p} alone")
-                assert (outs[p].float() - o1.float()).abs().max().item() <= 2e-2 * max(1.0, float(abs(ref).max()))
-    finally:
-        os.environ.pop("DZ_SPLITS", None)
+    with dz.Context(0) as c:
+        if splits != "auto":
+            c.set_option(dz.DZ_OPT_SPLIT_K, int(splits))
+        cases = _make(dz, c, group)
+        x, idv = cases[0].x, cases[0].ids
+        outs = [cs.out(fill=7.0) for cs in cases]
+        dz.dz_linear_group(c.h, cases[0].dx, [cs.dW for cs in cases], [cs.packed for cs in cases], cases[0].dids,
+                           outs, T, Ns, K, bits, G)
+        assert dz.dz_check(c.h) == dz.DZ_OK
+        for p, cs in enumerate(cases):
+            ref = _oracle(cs, x, idv)
+            assert_close(outs[p], ref, f"{name} projection {p}")
+            # and the single-projection entry point agrees to within the same bar
+            o1 = cs.out(fill=7.0)
+            dz.dz_linear(c.h, cases[0].dx, cs.dW, cs.packed, cases[0].dids, o1, T, cs.N, K, bits, G)
+            assert_close(o1, ref, f"{name} projection {p} alone")
+            assert (outs[p].float() - o1.float()).abs().max().item() <= 2e-2 * max(1.0, float(abs(ref).max()))
 
 
 def test_group_argument_errors(dz):

@@ -1,8 +1,6 @@
 """GPU parity: dz_base_gemm, dz_sbmm and dz_linear against the CPU oracle on the same seeded inputs
 (paper Section 5.1 Eq. (2), Section 5.2).  Sizes the oracle finishes in seconds, chosen to span
 several row tiles, k tiles, column blocks, split and unsplit k, and ragged request counts."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -50,17 +48,12 @@ def _run_all(dz, c, cs, tag):
 def test_parity_small(dz, case, splits):
     name, T, N, K, D, bits, G, ids = case
     print(f"case {name} splits={splits}", flush=True)
-    if splits == "auto":
-        os.environ.pop("DZ_SPLITS", None)
-    else:
-        os.environ["DZ_SPLITS"] = splits
-    try:
-        with dz.Context(0) as c:
-            cs = Case(dz, c.h, 0, T, N, K, D, bits, G, ids)
-            max_rel, mean_abs = _run_all(dz, c, cs, name)
-            print(f"  linear max_rel={max_rel:.2e} mean_abs={mean_abs:.2e}", flush=True)
-    finally:
-        os.environ.pop("DZ_SPLITS", None)
+    with dz.Context(0) as c:
+        if splits != "auto":
+            c.set_option(dz.DZ_OPT_SPLIT_K, int(splits))
+        cs = Case(dz, c.h, 0, T, N, K, D, bits, G, ids)
+        max_rel, mean_abs = _run_all(dz, c, cs, name)
+        print(f"  linear max_rel={max_rel:.2e} mean_abs={mean_abs:.2e}", flush=True)
 
 
 def test_single_rounding_is_tight(dz):
@@ -166,26 +159,56 @@ def test_tiles_of_one_delta(dz):
         _run_all(dz, c, cs, "mixed tiles")
 
 
-@pytest.mark.parametrize("env", [{"DZ_TILE": "2"}, {"DZ_TILE": "2", "DZ_SPLITS": "3"}, {"DZ_TILE": "2", "DZ_SPLITS": "1"}, {}],
+@pytest.mark.parametrize("opts", [{"DZ_OPT_WIDE_TILE": 2}, {"DZ_OPT_WIDE_TILE": 2, "DZ_OPT_SPLIT_K": 3},
+                                  {"DZ_OPT_WIDE_TILE": 2, "DZ_OPT_SPLIT_K": 1}, {}],
                          ids=["wide", "wide_splits3", "wide_whole", "default"])
-def test_base_gemm_of_a_large_batch_over_several_tiles(dz, env):
+def test_base_gemm_of_a_large_batch_over_several_tiles(dz, opts):
     """The base product of a large batch (Eq. (2), first term): several 256 x 256 tiles with ragged
-    last tiles in both directions, whole and cut into k slices (DZ_TILE=2 sends every such call to
-    the 256 x 256 kernel, which by default only takes calls with many tiles), and the default route."""
+    last tiles in both directions, whole and cut into k slices (DZ_OPT_WIDE_TILE = 2 sends every such
+    call to the 256 x 256 kernel, which by default only takes calls with many tiles), and the default
+    route."""
     import oracle
     T, N, K = 600, 784, 1024
-    print(f"wide base gemm {env}", flush=True)
-    for k, v in env.items():
-        os.environ[k] = v
-    try:
-        with dz.Context(0) as c:
-            W = S.make_base(N, K, S.stream(70, "W"), 0.02)
-            x = S.make_x(T, K, S.stream(70, "x"))
-            ref = oracle.c.linear(x.numpy(), W.numpy(), None, None)
-            o = torch.full((T, N), 7.0, dtype=torch.float16, device="cuda")
-            dz.dz_base_gemm(c.h, x.cuda(), W.cuda(), o, T, N, K)
-            assert dz.dz_check(c.h) == dz.DZ_OK
-            assert_close(o, ref, f"base gemm {env}")
-    finally:
-        for k in env:
-            os.environ.pop(k, None)
+    print(f"wide base gemm {opts}", flush=True)
+    with dz.Context(0) as c:
+        for k, v in opts.items():
+            c.set_option(getattr(dz, k), v)
+        W = S.make_base(N, K, S.stream(70, "W"), 0.02)
+        x = S.make_x(T, K, S.stream(70, "x"))
+        ref = oracle.c.linear(x.numpy(), W.numpy(), None, None)
+        o = torch.full((T, N), 7.0, dtype=torch.float16, device="cuda")
+        dz.dz_base_gemm(c.h, x.cuda(), W.cuda(), o, T, N, K)
+        assert dz.dz_check(c.h) == dz.DZ_OK
+        assert_close(o, ref, f"base gemm {opts}")
+
+
+def test_options_are_validated(dz):
+    with dz.Context(0) as c:
+        assert c.set_option(dz.DZ_OPT_SPLIT_K, 3) == dz.DZ_OK
+        assert dz.dz_set_option(c.h, dz.DZ_OPT_WIDE_TILE, 3, check=False) == dz.DZ_ERR_ARG
+        assert dz.dz_set_option(c.h, dz.DZ_OPT_WG_SHAPE, 44, check=False) == dz.DZ_ERR_ARG
+        assert dz.dz_set_option(c.h, 99, 1, check=False) == dz.DZ_ERR_ARG
+        assert dz.dz_set_option(c.h, dz.DZ_OPT_SPLIT_K, -1, check=False) == dz.DZ_ERR_ARG
+
+
+def test_large_batch_calls_of_one_layer_share_one_sort(dz):
+    """DZ_OPT_REUSE_SEGMENTS: consecutive large-batch calls with the same index vector reuse the
+    sorted order; a changed vector at another address, another T or a reset option sorts again."""
+    with dz.Context(0) as c:
+        c.set_option(dz.DZ_OPT_REUSE_SEGMENTS, 1)
+        a = Case(dz, c.h, 31, 300, 64, 512, 5, 4, 128, "segments")
+        b = Case(dz, c.h, 32, 300, 96, 512, 5, 4, 128, "uniform")
+        for rep in range(2):
+            for cs in (a, a, b, a):
+                o = cs.out(fill=7.0)
+                dz.dz_linear(c.h, cs.dx, cs.dW, cs.packed, cs.dids, o, cs.T, cs.N, cs.K, cs.bits, cs.G)
+                assert_close(o, cs.y, "reuse")
+        # same address, new contents: the caller must reset the option (its promise no longer holds)
+        a.dids.copy_(b.dids)
+        c.set_option(dz.DZ_OPT_REUSE_SEGMENTS, 1)
+        import oracle
+        ref = oracle.c.linear(a.x.numpy(), a.W.numpy(), a.dense, b.ids.numpy())
+        o = a.out(fill=7.0)
+        dz.dz_linear(c.h, a.dx, a.dW, a.packed, a.dids, o, a.T, a.N, a.K, a.bits, a.G)
+        assert_close(o, ref, "after reset")
+        assert dz.dz_check(c.h) == dz.DZ_OK
