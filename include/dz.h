@@ -66,6 +66,7 @@ extern "C" {
 
 #define DZ_MAX_DELTAS 128   /* deltas resident for one call                                          */
 #define DZ_MAX_GROUP  4     /* projections in one dz_linear_group call                               */
+#define DZ_STATIC_PARTIAL_BYTES ((size_t)32 << 20)   /* split-k room of dz_linear_static                   */
 
 typedef struct dz_ctx dz_ctx;
 
@@ -179,6 +180,23 @@ int dz_linear(dz_ctx *ctx, const void *x_f16, const void *W_f16, const void *con
 int dz_linear_group(dz_ctx *ctx, const void *x_f16, int P, const void *const *W_f16,
                     const void *const *packed_deltas, int D, const int32_t *token_to_delta,
                     void *const *out_f16, const int *N, int T, int K, int bits, int group, void *stream);
+
+/*
+ * dz_linear for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  It takes no context; the workspace the kernels need (split-k
+ * partial sums, arrival counters, the error word) is a static device array of the library, fixed at
+ * DZ_STATIC_PARTIAL_BYTES + 64.25 KiB per GPU, which every GPU the library runs on holds until the
+ * process ends.  The call allocates nothing, frees nothing and synchronises nothing.
+ * Arguments as dz_linear, with `device` in place of the context.  Limits: T <= 64, and the split-k
+ * partial sums of the call (a multiple of 64 * N * 4 bytes, chosen from N and K) must fit the array;
+ * beyond either the call returns DZ_ERR_LIMIT and enqueues no compute.  All calls on one GPU share that
+ * GPU's array: two calls whose kernels may overlap on one GPU (different streams, different
+ * threads) race and must be serialised by the caller.  A request index outside [-1, D) is served
+ * with the base model only and reported by the next dz_check on any context of that GPU.
+ */
+int dz_linear_static(int device, const void *x_f16, const void *W_f16, const void *const *packed_deltas,
+                     int D, const int32_t *token_to_delta, void *out_f16, int T, int N, int K, int bits,
+                     int group, void *stream);
 
 /* Synchronise `stream`; return DZ_ERR_INDEX if any call since the last dz_check met a request
  * index outside [-1, D) (that request was served with the base model only), else DZ_OK. */

@@ -9,7 +9,7 @@ import torch
 __all__ = [
     "DZ_OK", "DZ_ERR_ARG", "DZ_ERR_SHAPE", "DZ_ERR_BITS", "DZ_ERR_ALIGN", "DZ_ERR_HIP", "DZ_ERR_INDEX", "DZ_ERR_LIMIT",
     "DZ_OPT_SPLIT_K", "DZ_OPT_WORKGROUPS", "DZ_OPT_ROUND_TILES", "DZ_OPT_LARGE_BATCH_STREAMING", "DZ_OPT_WIDE_TILE",
-    "DZ_OPT_REUSE_SEGMENTS", "DZ_OPT_WG_SHAPE", "dz_set_option", "dz_probe_read", "dz_probe_mfma",
+    "DZ_OPT_REUSE_SEGMENTS", "DZ_OPT_WG_SHAPE", "dz_set_option", "dz_linear_static", "dz_probe_read", "dz_probe_mfma",
     "DZ_MAX_DELTAS", "DzError", "lib", "lib_path", "dz_strerror", "dz_create", "dz_destroy",
     "dz_packed_bytes", "dz_pack_delta", "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm",
     "dz_linear", "dz_linear_group", "dz_check", "Context", "SYMBOLS", "DZ_MAX_GROUP",
@@ -22,7 +22,7 @@ DZ_OK, DZ_ERR_ARG, DZ_ERR_SHAPE, DZ_ERR_BITS, DZ_ERR_ALIGN, DZ_ERR_HIP, DZ_ERR_I
 DZ_MAX_DELTAS = 128
 DZ_MAX_GROUP = 4
 
-SYMBOLS = ["dz_strerror", "dz_last_hip_error", "dz_create", "dz_destroy", "dz_set_option", "dz_probe_read", "dz_probe_mfma", "dz_packed_bytes", "dz_pack_delta",
+SYMBOLS = ["dz_strerror", "dz_last_hip_error", "dz_create", "dz_destroy", "dz_set_option", "dz_linear_static", "dz_probe_read", "dz_probe_mfma", "dz_packed_bytes", "dz_pack_delta",
            "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm", "dz_linear", "dz_linear_group", "dz_check",
            "dz_cache_create", "dz_cache_destroy", "dz_cache_acquire", "dz_cache_wait", "dz_cache_release",
            "dz_cache_stats"]
@@ -71,6 +71,7 @@ def lib() -> ctypes.CDLL:
         L.dz_set_option.argtypes = [vp, ci, ci]
         L.dz_probe_read.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.dz_probe_mfma.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double), vp]
+        L.dz_linear_static.argtypes = [ci, vp, vp, ctypes.POINTER(vp), ci, vp, vp, ci, ci, ci, ci, ci, vp]
         i64p, i32p = ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32)
         L.dz_cache_create.argtypes = [ctypes.POINTER(vp), ci, ci, ctypes.c_size_t]
         L.dz_cache_destroy.argtypes = [vp]
@@ -191,6 +192,14 @@ def dz_linear(ctx, x, W, packed_deltas, token_to_delta, out, T, N, K, bits, grou
     rc = lib().dz_linear(ctx, _ptr(x), _ptr(W), arr, D, _ptr(token_to_delta), _ptr(out), T, N, K, bits, group,
                          _stream(stream))
     return _raise(ctx, rc, "dz_linear", check)
+
+
+def dz_linear_static(device: int, x, W, packed_deltas, token_to_delta, out, T, N, K, bits, group, stream=None,
+                     check=True) -> int:
+    arr, D = _ptr_array(packed_deltas)
+    rc = lib().dz_linear_static(int(device), _ptr(x), _ptr(W), arr, D, _ptr(token_to_delta), _ptr(out), T, N, K, bits,
+                                group, _stream(stream))
+    return _raise(None, rc, "dz_linear_static", check)
 
 
 def dz_linear_group(ctx, x, W_list, packed_deltas_list, token_to_delta, out_list, T, N_list, K, bits, group,
