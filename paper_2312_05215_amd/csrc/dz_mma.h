@@ -216,6 +216,12 @@ __device__ __forceinline__ void advance(Cursor &c, int kr0, int kr1)
     if (++c.kt == kr1) { c.kt = kr0; ++c.seg; }
 }
 
+// k-tile-major order: the segments lo .. hi - 1 of a k tile, then the next k tile
+__device__ __forceinline__ void advance_seg(Cursor &c, int lo, int hi)
+{
+    if (++c.seg >= hi) { c.seg = lo; ++c.kt; }
+}
+
 __device__ __forceinline__ void store_row4(_Float16 *p, f4 v, int accumulate)
 {
     typedef _Float16 h4 __attribute__((ext_vector_type(4)));

@@ -43,35 +43,23 @@ struct SegTable {
     int sb, se;             // sorted positions [sb, se)
 };
 
-template <int J>
-struct Task {
-    int boff[J];            // per lane and column block: LDS offset (halfs) of the x row it multiplies,
-                            // the zero row if its sorted position is not in the segment
-    int kofs;               // offset of the task's k tile in the LDS slice (halfs)
-};
+// The delta phase works on *windows* of two column blocks (32 sorted request positions).  The B
+// fragments of one k tile for the window's column blocks and all four steps are held in registers
+// (64 per wave) for as long as that k tile's segments are multiplied: every segment's sparse MFMAs
+// read them from there, so the delta phase reads x from LDS once per k tile and window instead of
+// once per segment.  A batch of more than 32 rows has two windows; the sorted order makes the
+// segments that overlap a window a contiguous run of the segment table, so each window streams only
+// its own segments' packed tiles (a segment that straddles position 32 is streamed by both).
+constexpr int WIN = 2;              // column blocks per window
 
-template <int J>
-__device__ __forceinline__ void task_setup(const Cursor &c, int kr0, const SegTable &tab, const int (&brow)[J], int zoff,
-                                           const Geo &g, Task<J> &t)
-{
-    const int sb = __builtin_amdgcn_readlane(tab.sb, c.seg);
-    const int se = __builtin_amdgcn_readlane(tab.se, c.seg);
-    t.kofs = (c.kt - kr0) * 256;
-#pragma unroll
-    for (int j = 0; j < J; ++j) {
-        const int pos = 16 * j + g.row;
-        t.boff[j] = (pos >= sb && pos < se) ? brow[j] : zoff;
-    }
-}
-
-// B fragments of step s of a task, all column blocks (a block the segment does not touch reads
-// the zero row in every lane and adds nothing: with at most four blocks that costs less than the
-// branches and register copies a per-block skip would put between the MFMAs).
-template <int J>
-__device__ __forceinline__ void task_frags(const Task<J> &t, const _Float16 *xs, const Geo &g, int s, h16 (&b)[J])
+template <int J, int J0, int JW>
+__device__ __forceinline__ void load_window_frags(const _Float16 *xs, const int (&brow)[J], const Geo &g, int kofs,
+                                                  h16 (&bf)[4][WIN])
 {
 #pragma unroll
-    for (int j = 0; j < J; ++j) b[j] = load_b(xs, t.boff[j], g, t.kofs + s * 64);
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int j = 0; j < JW; ++j) bf[s][j] = load_b(xs, brow[J0 + j], g, kofs + s * 64);
 }
 
 template <int BITS, int GROUP, int R>
@@ -106,24 +94,23 @@ __device__ __forceinline__ void stream_delta_issue(const Cursor &c, bool valid, 
     }
 }
 
-// The four steps of task `t` (stage registers st) accumulated straight into acc: lanes of request
-// rows outside the segment multiply the zero row.  b0 holds the fragments of step 0 on entry; each
-// step first sends out the LDS reads of the next step -- after step 3 those of step 0 of the next
-// task `tn` -- so that a read is never waited for right after it is issued.  The two fragment
-// buffers alternate; after four steps b0 is the live one again.
-template <int BITS, int GROUP, int R, int J>
-__device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], const Task<J> &t,
-                                                  const Task<J> &tn, const _Float16 *xs, const Geo &g, h16 (&b0)[J],
-                                                  h16 (&b1)[J], f4 (&acc)[R][J])
+// The four steps of one packed tile (stage registers st) of the segment [sb, se) of sorted positions,
+// against the window of column blocks J0 .. J0 + JW - 1.  The sparse MFMAs multiply all request columns
+// of the window (the fragments in registers are not masked) into a copy of the accumulators; lanes
+// whose request column lies in the segment then keep the copy, the others keep what they had: one
+// select per accumulator register and task instead of a masked read of x per step.
+template <int BITS, int GROUP, int R, int J, int J0, int JW>
+__device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], int sb, int se,
+                                                  const h16 (&bf)[4][WIN], const Geo &g, f4 (&acc)[R][J])
 {
     typedef Fmt<BITS, GROUP> F;
+    f4 tmp[R][JW];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < JW; ++j) tmp[r][j] = acc[r][J0 + j];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-        if (s == 0) task_frags<J>(t, xs, g, 1, b1);
-        else if (s == 1) task_frags<J>(t, xs, g, 2, b0);
-        else if (s == 2) task_frags<J>(t, xs, g, 3, b1);
-        else task_frags<J>(tn, xs, g, 0, b0);
-        __builtin_amdgcn_sched_barrier(0);
         h8 av[R];
         uint32_t idxw[R];
 #pragma unroll
@@ -137,22 +124,33 @@ __device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BI
             av[r] = dequant_step<BITS>(w, s2, z2);
         }
 #pragma unroll
-        for (int j = 0; j < J; ++j) {
+        for (int j = 0; j < JW; ++j) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                if (s & 1) acc[r][j] = smfmac<1>(av[r], b1[j], acc[r][j], (int)idxw[r]);
-                else acc[r][j] = smfmac<0>(av[r], b0[j], acc[r][j], (int)idxw[r]);
+                if (s & 1) tmp[r][j] = smfmac<1>(av[r], bf[s][j], tmp[r][j], (int)idxw[r]);
+                else tmp[r][j] = smfmac<0>(av[r], bf[s][j], tmp[r][j], (int)idxw[r]);
             }
         }
-        __builtin_amdgcn_sched_barrier(0);
+    }
+    const unsigned len = (unsigned)(se - sb);
+#pragma unroll
+    for (int j = 0; j < JW; ++j) {
+        const bool in = (unsigned)(16 * (J0 + j) + g.row - sb) < len;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            acc[r][J0 + j].x = in ? tmp[r][j].x : acc[r][J0 + j].x;
+            acc[r][J0 + j].y = in ? tmp[r][j].y : acc[r][J0 + j].y;
+            acc[r][J0 + j].z = in ? tmp[r][j].z : acc[r][J0 + j].z;
+            acc[r][J0 + j].w = in ? tmp[r][j].w : acc[r][J0 + j].w;
+        }
     }
 }
 
-// Tuned constants: k tiles of x an LDS round may hold for the one- and two-column-block shapes
-// (T <= 32; 8: 135 KB, one workgroup per CU), and packed-tile stage buffers of the delta phase (3:
-// two tiles in flight while one computes; 4 and 5 measured 1-7 % slower on every shape at eight
-// waves per CU).
+// Tuned constants: k tiles of x an LDS round may hold (8 for one or two column blocks, 4 for three
+// or four: 135 KB either way, one workgroup per CU), and packed-tile stage buffers of the delta
+// phase (3: two tiles in flight while one computes).
 constexpr int DZ_RCAP_SMALL = 8;
+constexpr int DZ_RCAP_LARGE = 4;
 constexpr int DSTG = 3;
 template <int BITS, int GROUP, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
@@ -238,6 +236,9 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     bool tables_ready = !sort_here;
     bool first_round = true;
     int nseg = 0;
+    // segments of the sorted order that overlap window 0 (positions 0 .. 31) and window 1 (32 .. 63)
+    constexpr int NW = (J + WIN - 1) / WIN;
+    int wlo0 = 0, whi0 = 0, wlo1 = 0, whi1 = 0, ns0 = 0, ns1 = 0;
     int brow[J];
 #pragma unroll
     for (int j = 0; j < J; ++j) brow[j] = 0;
@@ -277,9 +278,12 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         const int kr1 = min(kt1, kr0 + round_tiles);
         const int ntr = kr1 - kr0;
         const int nsteps = 4 * ntr;              // base steps of this round
-        int nd = nseg * ntr;                     // delta tasks of this round (set after the sort in round one)
+        // Delta tasks of this round, in issue order: window 0's (k tile by k tile, all of its segments per
+        // k tile), padded to a multiple of the stage-buffer count so that window 1's start at rotation
+        // phase 0, then window 1's.  Set after the sort in round one.
+        int nd0 = ns0 * ntr, nd0p = NW > 1 ? (nd0 + DSTG - 1) / DSTG * DSTG : nd0, nd = nd0p + ns1 * ntr;
         Cursor ci, cc;
-        ci.kt = kr0; ci.seg = 0;
+        ci.kt = kr0; ci.seg = wlo0;
         cc = ci;
         // named stage buffers (so each stays in registers), rotated by hand.  Issue cursors stop at
         // the last task / step and re-issue it (a few redundant cache hits at the end of a round)
@@ -290,22 +294,28 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
 #pragma unroll
         for (int r = 0; r < R; ++r) wbase[r] = ((uint32_t)rtc[r] * 16u * (uint32_t)a.K + (uint32_t)kr0 * 256u) * 2u;
         int ti = 0, tc = 0;
+        // the issue cursor walks the same order two tasks ahead of the multiplying one; in the padding
+        // and past the end the loads are issued against an empty resource
 #define DZ_ISSUE(buf)                                                                                              \
     do {                                                                                                           \
-        stream_delta_issue<BITS, GROUP, R>(ci, nd > 0, g, rtc, lo, tab, off_idx, off_scale, blob_bytes, buf);      \
-        if (++ti < nd) advance(ci, kr0, kr1);                                                                      \
+        const bool live = ti < nd0 || (ti >= nd0p && ti < nd);                                                     \
+        stream_delta_issue<BITS, GROUP, R>(ci, live, g, rtc, lo, tab, off_idx, off_scale, blob_bytes, buf);        \
+        ++ti;                                                                                                      \
+        if (NW > 1 && ti == nd0p) { ci.kt = kr0; ci.seg = wlo1; }                                                  \
+        else if (ti < nd0) advance_seg(ci, wlo0, whi0);                                                            \
+        else if (NW > 1 && ti > nd0p && ti < nd) advance_seg(ci, wlo1, whi1);                                      \
     } while (0)
-#define DZ_STEP(cur, nxt)                                                                                          \
+#define DZ_STEP(W, cur, nxt)                                                                                       \
     do {                                                                                                           \
+        constexpr int J0 = (W) * WIN, JW = (J - J0 < WIN) ? J - J0 : WIN;                                          \
+        const int slo = (W) ? wlo1 : wlo0, shi = (W) ? whi1 : whi0;                                                \
         DZ_ISSUE(nxt);                                                                                             \
-        if (tc < nd) {                                                                                             \
-            Cursor cn = cc;                                                                                        \
-            if (tc + 1 < nd) advance(cn, kr0, kr1);     /* after the last task: the same one again, unused */     \
-            Task<J> tn;                                                                                            \
-            task_setup<J>(cn, kr0, tab, brow, ZROW * g.LDW, g, tn);                                                \
-            stream_delta_task<BITS, GROUP, R, J>(cur, tk, tn, xs, g, bq, bq1, acc);                                     \
-            tk = tn;                                                                                               \
-            cc = cn;                                                                                               \
+        if (tc < ((W) ? nd : nd0)) {                                                                               \
+            if (cc.seg == slo) load_window_frags<J, J0, JW>(xs, brow, g, (cc.kt - kr0) * 256, bf);  /* new k tile */ \
+            const int sb = __builtin_amdgcn_readlane(tab.sb, cc.seg);                                              \
+            const int se = __builtin_amdgcn_readlane(tab.se, cc.seg);                                              \
+            stream_delta_task<BITS, GROUP, R, J, J0, JW>(cur, sb, se, bf, g, acc);                                 \
+            advance_seg(cc, slo, shi);                                                                             \
         }                                                                                                          \
         ++tc;                                                                                                      \
     } while (0)
@@ -324,7 +334,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         // two batches of loads per thread cover the largest round: the first is written to LDS
         // right away, the second stays in registers while the weight prefetch is issued behind it
         // (one batch for the whole slice would not fit the registers next to that prefetch)
-        constexpr int XB = (16 * J * ((J <= 2) ? DZ_RCAP_SMALL : 2) * 32 + 2 * THREADS - 1) / (2 * THREADS);
+        constexpr int XB = (16 * J * ((J <= 2) ? DZ_RCAP_SMALL : DZ_RCAP_LARGE) * 32 + 2 * THREADS - 1) / (2 * THREADS);
         u32x4 xv[XB];
         int xdst[XB];
 #define DZ_XLOAD(i0)                                                                                               \
@@ -418,7 +428,22 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             lds_barrier();
             tables_ready = true;
             nseg = HAS_DELTA ? s_nseg : 0;
-            nd = nseg * ntr;
+            if constexpr (HAS_DELTA) {
+                // the segments are in position order: those that begin below 32 come first, those that
+                // end above 32 come last
+                const bool mine = g.lane < nseg;
+                const int sbl = mine ? s_seg_begin[g.lane] : 0, sel = mine ? s_seg_begin[g.lane + 1] : 0;
+                const unsigned long long m0 = __ballot(mine && sbl < 16 * WIN);
+                const unsigned long long m1 = __ballot(mine && sel > 16 * WIN);
+                whi0 = __builtin_popcountll(m0);
+                if (NW > 1 && m1) { wlo1 = (int)__builtin_ctzll(m1); whi1 = nseg; }
+                ns0 = whi0 - wlo0;
+                ns1 = whi1 - wlo1;
+            }
+            nd0 = ns0 * ntr;
+            nd0p = NW > 1 ? (nd0 + DSTG - 1) / DSTG * DSTG : nd0;
+            nd = nd0p + ns1 * ntr;
+            ci.seg = cc.seg = wlo0;
 #pragma unroll
             for (int j = 0; j < J; ++j) brow[j] = s_boff[16 * j + g.row];
         }
@@ -451,15 +476,20 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             }
         }
         if constexpr (HAS_DELTA) {
-            Task<J> tk;
-            h16 bq[J], bq1[J];
-            task_setup<J>(cc, kr0, tab, brow, ZROW * g.LDW, g, tk);
-            task_frags<J>(tk, xs, g, 0, bq);
-            while (tc < nd) {
-                static_assert(DSTG == 3, "the rotation below is written for three stage buffers");
-                DZ_STEP(st0, st2);
-                DZ_STEP(st1, st0);
-                DZ_STEP(st2, st1);
+            static_assert(DSTG == 3, "the rotation below is written for three stage buffers");
+            h16 bf[4][WIN];
+            while (tc < nd0p) {
+                DZ_STEP(0, st0, st2);
+                DZ_STEP(0, st1, st0);
+                DZ_STEP(0, st2, st1);
+            }
+            if constexpr (NW > 1) {
+                cc.kt = kr0; cc.seg = wlo1;
+                while (tc < nd) {
+                    DZ_STEP(1, st0, st2);
+                    DZ_STEP(1, st1, st0);
+                    DZ_STEP(1, st2, st1);
+                }
             }
         }
 #undef DZ_ISSUE
@@ -600,11 +630,10 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group
     const int KT = a.K / 256;
     const int nchunks = (a.T + 63) / 64;
     const int J = (a.T >= 64) ? 4 : (a.T + 15) / 16;
-    // workgroup shape: one or two column blocks -> 8 waves x 1 row tile; three or four -> 4 waves x
-    // 2 row tiles (a packed tile's dequantisation set-up and each B fragment read from LDS serve two
-    // row tiles: measured 10-20 % faster there than 8 x 1)
+    // workgroup shape: 8 waves x 1 row tile (the B fragments of a k tile fill 32 J registers of every
+    // wave during the delta phase, which leaves room for one row tile's accumulators and stage buffers)
     int WAVES = ctx->wg_waves, R = ctx->wg_rtiles;
-    if (WAVES <= 0 || R <= 0) { WAVES = (J <= 2) ? 8 : 4; R = (J <= 2) ? 1 : 2; }
+    if (WAVES <= 0 || R <= 0) { WAVES = 8; R = 1; }
     // row blocks of the projections, one projection after the other; a row block never spans two
     int NRB = 0, n_total = 0;
     for (int p = 0; p < gp.P; ++p) {
@@ -640,7 +669,7 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group
     if ((size_t)max_slots * Tp * a.N * 4 >= ((size_t)1 << 32)) return DZ_ERR_SHAPE;    // 32-bit byte offsets
     if ((unsigned long long)a.T * a.K * 2ull >= 0xFFFFFFF0ull) return DZ_ERR_SHAPE;
     // one batch of x loads per thread must cover a round (see XB in the kernel)
-    const int round_cap = (J <= 2 ? DZ_RCAP_SMALL : 2);
+    const int round_cap = (J <= 2 ? DZ_RCAP_SMALL : DZ_RCAP_LARGE);
     int round_tiles = (ctx->round_tiles > 0 && ctx->round_tiles < round_cap) ? ctx->round_tiles : round_cap;
     const int max_slice = (int)((P + G - 1) / G) < KT ? (int)((P + G - 1) / G) : KT;
     if (round_tiles > max_slice) round_tiles = max_slice;
