@@ -123,7 +123,7 @@ def quantize_groups(kept: torch.Tensor, bits: int, group: int):
     dead = s16 == 0
     s16 = torch.where(dead, torch.ones_like(s16), s16)
     s = s16.to(torch.float32)
-    z = torch.clamp(torch.round(-lo / s), 0.0, qmax)      # torch.round is round-half-even
+    z = torch.clamp(torch.round((0.0 - lo) / s), 0.0, qmax)      # torch.round is round-half-even
     z = torch.where(dead, torch.zeros_like(z), z)
     q = torch.clamp(torch.round(v / s.unsqueeze(-1)) + z.unsqueeze(-1), 0.0, qmax)
     return (q.to(torch.uint8).reshape(N, K2), s16, z.to(torch.float16))

@@ -117,6 +117,19 @@ int dz_pack_delta(dz_ctx *ctx, const uint8_t *codes, const uint8_t *idx, const v
                   void *stream);
 
 /*
+ * The data-free compressor: a dense fp16 delta [N][K] (DEVICE, 8-byte aligned) -> the canonical tables
+ * dz_pack_delta takes (all DEVICE, caller-allocated).  Section 4.1 step 2 prunes the delta to the 2:4
+ * pattern and step 3 quantises the kept values; Algorithm 1 chooses mask and codes with calibration
+ * data, this call applies the rule that needs none: per group of four keep the two entries of largest
+ * magnitude (ties: the lower position), then per row and `group` dense columns an asymmetric uniform grid
+ * that contains zero, rounded to nearest (half to even) in fp32:
+ *   s = f16((hi - lo) / (2^bits - 1)) with lo = min(0, min v), hi = max(0, max v) over the group's kept
+ *   values (s = 1, z = 0 if that is zero), z = clamp(rint((0 - lo) / s)) (never a negative zero), code = clamp(rint(v / s) + z).
+ */
+int dz_compress_delta(dz_ctx *ctx, const void *delta_f16, int N, int K, int bits, int group,
+                      uint8_t *codes, uint8_t *idx, void *scale_f16, void *zero_f16, void *stream);
+
+/*
  * Inverse of dz_pack_delta, for checking: any output may be NULL.  codes/idx/scale/zero reproduce
  * the canonical tables bit for bit; dense_f32 [N][K] is the matrix the delta stands for, computed
  * in fp32 (exact, see the value formula above).  All pointers DEVICE.
@@ -162,6 +175,20 @@ int dz_sbmm(dz_ctx *ctx, const void *x_f16, const void *const *packed_deltas, in
 int dz_linear(dz_ctx *ctx, const void *x_f16, const void *W_f16, const void *const *packed_deltas,
               int D, const int32_t *token_to_delta, void *out_f16, int T, int N, int K, int bits,
               int group, void *stream);
+
+/*
+ * Low-rank adapters in place of deltas (Section 3.2: adapters are registered and served next to deltas;
+ * Section 6.4).  For every request t with m = token_to_adapter[t] in [0, D)
+ *   y[t] = B_m . (A_m . x[t]),   A_m f16 [rank][K],  B_m f16 [N][rank],  fp32 accumulation,
+ * requests with m == -1 (or out of range, which dz_check reports) get y[t] = 0;
+ *   accumulate == 0 : out[t] = f16(y[t]);   accumulate != 0 : out[t] = f16(float(out[t]) + y[t]),
+ * so a base product or a dz_linear result can be completed in place.  A and B are HOST arrays of D
+ * DEVICE pointers (16-byte aligned, read before the call returns).  rank in {8, 16, ..., 64};
+ * K % 8 == 0; N % 4 == 0; out 8-byte aligned.  The batch is walked in adapter-sorted order.
+ */
+int dz_lora_sbmm(dz_ctx *ctx, const void *x_f16, const void *const *A_f16, const void *const *B_f16, int D,
+                 int rank, const int32_t *token_to_adapter, void *out_f16, int T, int N, int K,
+                 int accumulate, void *stream);
 
 /*
  * Several linear layers that read the same x for the same requests -- the q, k, v projections of a

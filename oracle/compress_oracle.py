@@ -10,7 +10,7 @@ data-free rule this build uses everywhere a compressed delta is needed:
           position wins), listed in ascending position;
   step 3  per row and per `group` dense columns (= group/2 kept values) an asymmetric uniform grid that
           contains zero:  lo = min(0, min v), hi = max(0, max v),  s = f16((hi - lo) / (2^b - 1))
-          (s = 1, z = 0 if that is zero),  z = clamp(rint(-lo / s), 0, 2^b - 1),
+          (s = 1, z = 0 if that is zero),  z = clamp(rint((0 - lo) / s), 0, 2^b - 1),
           q = clamp(rint(v / s) + z, 0, 2^b - 1);  rint rounds half to even; arithmetic in fp32.
 
 Output: the canonical tables (codes u8 [N][K/2], idx u8 [N][K/2], scale f16 [N][K/G], zero f16
@@ -58,7 +58,7 @@ def quantize(kept: np.ndarray, bits: int, group: int):
         dead = s16 == 0
         s16 = np.where(dead, np.float16(1), s16)
         s = s16.astype(np.float32)
-        z = np.clip(np.rint(-lo / s), np.float32(0), qmax)
+        z = np.clip(np.rint((np.float32(0) - lo) / s), np.float32(0), qmax)
         z = np.where(dead, np.float32(0), z)
         q = np.clip(np.rint(v / s[:, None]) + z[:, None], np.float32(0), qmax)
         codes[:, gq * per:(gq + 1) * per] = q.astype(np.uint8)

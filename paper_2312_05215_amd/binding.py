@@ -9,7 +9,7 @@ import torch
 __all__ = [
     "DZ_OK", "DZ_ERR_ARG", "DZ_ERR_SHAPE", "DZ_ERR_BITS", "DZ_ERR_ALIGN", "DZ_ERR_HIP", "DZ_ERR_INDEX", "DZ_ERR_LIMIT",
     "DZ_OPT_SPLIT_K", "DZ_OPT_WORKGROUPS", "DZ_OPT_ROUND_TILES", "DZ_OPT_LARGE_BATCH_STREAMING", "DZ_OPT_WIDE_TILE",
-    "DZ_OPT_REUSE_SEGMENTS", "DZ_OPT_WG_SHAPE", "dz_set_option", "dz_linear_static", "dz_probe_read", "dz_probe_mfma",
+    "DZ_OPT_REUSE_SEGMENTS", "DZ_OPT_WG_SHAPE", "dz_set_option", "dz_linear_static", "dz_probe_read", "dz_probe_mfma", "dz_compress_delta", "dz_lora_sbmm",
     "DZ_MAX_DELTAS", "DzError", "lib", "lib_path", "dz_strerror", "dz_create", "dz_destroy",
     "dz_packed_bytes", "dz_pack_delta", "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm",
     "dz_linear", "dz_linear_group", "dz_check", "Context", "SYMBOLS", "DZ_MAX_GROUP",
@@ -22,7 +22,8 @@ DZ_OK, DZ_ERR_ARG, DZ_ERR_SHAPE, DZ_ERR_BITS, DZ_ERR_ALIGN, DZ_ERR_HIP, DZ_ERR_I
 DZ_MAX_DELTAS = 128
 DZ_MAX_GROUP = 4
 
-SYMBOLS = ["dz_strerror", "dz_last_hip_error", "dz_create", "dz_destroy", "dz_set_option", "dz_linear_static", "dz_probe_read", "dz_probe_mfma", "dz_packed_bytes", "dz_pack_delta",
+SYMBOLS = ["dz_strerror", "dz_last_hip_error", "dz_create", "dz_destroy", "dz_set_option", "dz_linear_static", "dz_probe_read", "dz_probe_mfma",
+           "dz_compress_delta", "dz_lora_sbmm", "dz_packed_bytes", "dz_pack_delta",
            "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm", "dz_linear", "dz_linear_group", "dz_check",
            "dz_cache_create", "dz_cache_destroy", "dz_cache_acquire", "dz_cache_wait", "dz_cache_release",
            "dz_cache_stats"]
@@ -69,6 +70,8 @@ def lib() -> ctypes.CDLL:
                                       ctypes.POINTER(ci), ci, ci, ci, ci, vp]
         L.dz_check.argtypes = [vp, vp]
         L.dz_set_option.argtypes = [vp, ci, ci]
+        L.dz_compress_delta.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp, vp]
+        L.dz_lora_sbmm.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, ci, vp, vp, ci, ci, ci, ci, vp]
         L.dz_probe_read.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.dz_probe_mfma.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double), vp]
         L.dz_linear_static.argtypes = [ci, vp, vp, ctypes.POINTER(vp), ci, vp, vp, ci, ci, ci, ci, ci, vp]
@@ -159,6 +162,22 @@ def dz_unpack_delta(ctx, packed, N, K, bits, group, codes=None, idx=None, scale=
     rc = lib().dz_unpack_delta(ctx, _ptr(packed), N, K, bits, group, _ptr(codes), _ptr(idx), _ptr(scale),
                                _ptr(zero), _ptr(dense_f32), _stream(stream))
     return _raise(ctx, rc, "dz_unpack_delta", check)
+
+
+def dz_compress_delta(ctx, delta, N, K, bits, group, codes, idx, scale, zero, stream=None, check=True) -> int:
+    rc = lib().dz_compress_delta(ctx, _ptr(delta), N, K, bits, group, _ptr(codes), _ptr(idx), _ptr(scale), _ptr(zero),
+                                 _stream(stream))
+    return _raise(ctx, rc, "dz_compress_delta", check)
+
+
+def dz_lora_sbmm(ctx, x, A_list, B_list, rank, token_to_adapter, out, T, N, K, accumulate=0, stream=None, check=True) -> int:
+    aarr, D = _ptr_array(A_list)
+    barr, Db = _ptr_array(B_list)
+    if D != Db:
+        raise ValueError("dz_lora_sbmm: one A and one B per adapter")
+    rc = lib().dz_lora_sbmm(ctx, _ptr(x), aarr, barr, D, int(rank), _ptr(token_to_adapter), _ptr(out), T, N, K,
+                            int(accumulate), _stream(stream))
+    return _raise(ctx, rc, "dz_lora_sbmm", check)
 
 
 def dz_segment(ctx, token_to_delta, T, D, counts=None, offsets=None, perm=None, stream=None, check=True) -> int:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdz.so")
-SOURCES = ["dz_api.hip", "dz_pack.hip", "dz_segment.hip", "dz_stream.hip", "dz_prefill.hip", "dz_tile.hip", "dz_cache.hip", "dz_probe.hip", "dz_static.hip"]
+SOURCES = ["dz_api.hip", "dz_pack.hip", "dz_segment.hip", "dz_stream.hip", "dz_prefill.hip", "dz_tile.hip", "dz_cache.hip", "dz_probe.hip", "dz_compress.hip", "dz_lora.hip", "dz_static.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

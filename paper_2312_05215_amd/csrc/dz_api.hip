@@ -379,6 +379,43 @@ int dz_linear_group(dz_ctx *ctx, const void *x, int P, const void *const *W, con
     return run_group(ctx, x, P, W, deltas, D, ids, out, N, T, K, bits, group, 0, true, true, (hipStream_t)stream);
 }
 
+int dz_compress_delta(dz_ctx *ctx, const void *delta, int N, int K, int bits, int group, uint8_t *codes, uint8_t *idx,
+                      void *scale, void *zero, void *stream)
+{
+    if (!ctx || !delta || !codes || !idx || !scale || !zero) return DZ_ERR_ARG;
+    int rc = check_shape(N, K, bits, group, true);
+    if (rc) return rc;
+    if ((reinterpret_cast<uintptr_t>(delta) & 7) || (reinterpret_cast<uintptr_t>(scale) & 1) || (reinterpret_cast<uintptr_t>(zero) & 1))
+        return DZ_ERR_ALIGN;
+    DeviceGuard guard(ctx->device);
+    return dz_launch_compress(ctx, delta, N, K, bits, group, codes, idx, scale, zero, (hipStream_t)stream);
+}
+
+int dz_lora_sbmm(dz_ctx *ctx, const void *x, const void *const *A, const void *const *B, int D, int rank,
+                 const int32_t *ids, void *out, int T, int N, int K, int accumulate, void *stream)
+{
+    if (!ctx || T < 0 || D < 0 || D > DZ_MAX_DELTAS) return DZ_ERR_ARG;
+    if (N <= 0 || K <= 0 || N % 4 != 0 || K % 8 != 0 || rank < 8 || rank > 64 || rank % 8 != 0) return DZ_ERR_SHAPE;
+    if (T == 0) return DZ_OK;
+    if (!x || !out || !ids || (D > 0 && (!A || !B))) return DZ_ERR_ARG;
+    if (!aligned16(x) || (reinterpret_cast<uintptr_t>(out) & 7) || (reinterpret_cast<uintptr_t>(ids) & 3)) return DZ_ERR_ALIGN;
+    for (int m = 0; m < D; ++m) {
+        if (!A[m] || !B[m]) return DZ_ERR_ARG;
+        if (!aligned16(A[m]) || !aligned16(B[m])) return DZ_ERR_ALIGN;
+    }
+    DeviceGuard guard(ctx->device);
+    hipStream_t st = (hipStream_t)stream;
+    int rc = ensure_seg(ctx, T, st);
+    if (rc) return rc;
+    rc = dz_ensure_lora(ctx, (size_t)T * rank * sizeof(float), st);
+    if (rc) return rc;
+    // the adapter-sorted order of the batch (Section 5.2: requests of one model are grouped)
+    rc = dz_launch_segment(ctx, ids, T, D, nullptr, nullptr, ctx->seg_perm, ctx->seg_key, st);
+    if (rc) return rc;
+    ctx->seg_ids = nullptr;         // the remembered order of DZ_OPT_REUSE_SEGMENTS is gone
+    return dz_launch_lora(ctx, x, A, B, D, rank, ids, ctx->seg_perm, ctx->lora_u, out, T, N, K, accumulate ? 1 : 0, st);
+}
+
 int dz_check(dz_ctx *ctx, void *stream)
 {
     if (!ctx) return DZ_ERR_ARG;

@@ -111,3 +111,7 @@ int dz_launch_stream(dz_ctx *, const DzStreamArgs &, const DzGroup &, const DzGr
 int dz_launch_prefill(dz_ctx *, const DzStreamArgs &, const DzDeltaPtrs &, hipStream_t);
 int dz_launch_tile(dz_ctx *, const DzStreamArgs &, hipStream_t);
 bool dz_tile_fits(const DzStreamArgs &);
+int dz_launch_compress(dz_ctx *, const void *delta, int N, int K, int bits, int group, uint8_t *codes, uint8_t *idx,
+                       void *scale, void *zero, hipStream_t);
+int dz_launch_lora(dz_ctx *, const void *x, const void *const *A, const void *const *B, int D, int rank, const int32_t *ids,
+                   const int32_t *perm, float *u, void *out, int T, int N, int K, int accumulate, hipStream_t);

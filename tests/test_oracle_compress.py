@@ -26,6 +26,8 @@ def test_hand_worked_groups():
     assert scale[:, 0].tolist() == [0.66650390625, 0.333251953125, 1.6669921875]
     assert zero[:, 0].tolist() == [2.0, 0.0, 2.0]
     assert codes.tolist() == [[0, 3], [3, 3], [0, 3]]
+    # a one-sided positive group has zero-point +0: the zero-point is one of the 2^b codes, never a negative zero
+    assert zero.view(np.uint16)[1, 0] == 0
     # an all-zero group: scale 1, zero 0, codes 0
     codes, scale, zero = C.quantize(np.zeros((1, 2), np.float16), 4, 4)
     assert (scale[0, 0], zero[0, 0], codes.tolist()) == (1.0, 0.0, [[0, 0]])
