@@ -144,6 +144,37 @@ def make_delta_tables(N: int, K: int, bits: int, group: int, gen: torch.Generato
                        bits, group)
 
 
+@dataclass
+class DenseTables:
+    """A quantisation-only delta (no 2:4 pruning): a code for every column."""
+    codes: torch.Tensor   # u8 [N][K]
+    scale: torch.Tensor   # f16 [N][K/G]
+    zero: torch.Tensor    # f16 [N][K/G]
+    bits: int
+    group: int
+
+    def to(self, device) -> "DenseTables":
+        return DenseTables(self.codes.to(device), self.scale.to(device), self.zero.to(device), self.bits, self.group)
+
+
+def make_dense_tables(N: int, K: int, bits: int, group: int, gen: torch.Generator, std: float = 0.002,
+                      row_chunk: int = 2048) -> DenseTables:
+    """Draw a delta ~ N(0, std) -> fp16 -> group-wise asymmetric RTN over all `group` values of a group."""
+    assert K % group == 0
+    codes, scales, zeros = [], [], []
+    for r0 in range(0, N, row_chunk):
+        r1 = min(N, r0 + row_chunk)
+        d = _normal_f16((r1 - r0, K), std, gen)
+        q, s, z = quantize_groups(d, bits, 2 * group)      # quantize_groups counts `group // 2` values per group
+        codes.append(q); scales.append(s); zeros.append(z)
+    return DenseTables(torch.cat(codes), torch.cat(scales), torch.cat(zeros), bits, group)
+
+
+def qpacked_bytes(N: int, K: int, bits: int, group: int) -> int:
+    """Bytes of a quantisation-only delta: b bits per weight plus one fp16 (scale, zero) pair per group."""
+    return N * K * bits // 8 + 4 * N * K // group
+
+
 # ----------------------------------------------------------------------------- request -> delta ids
 def ids_uniform(T: int, D: int, gen: torch.Generator) -> torch.Tensor:
     return torch.randint(0, D, (T,), generator=gen, device=gen.device, dtype=torch.int64).to(torch.int32)

@@ -93,7 +93,6 @@ int dz_destroy(dz_ctx *ctx);
 #define DZ_OPT_REUSE_SEGMENTS        6  /* 1 = the caller promises that a token_to_delta vector passed again at the same address
                                            with the same T and D is unchanged: consecutive large-batch calls of one layer then share
                                            one sort.  Setting the option (to either value) forgets the remembered order.             */
-#define DZ_OPT_WG_SHAPE              7  /* streaming kernel workgroup: 0 = chosen per call, 81 / 82 / 42 = waves x row tiles per wave */
 int dz_set_option(dz_ctx *ctx, int key, int value);
 
 /*
@@ -189,6 +188,40 @@ int dz_linear(dz_ctx *ctx, const void *x_f16, const void *W_f16, const void *con
 int dz_lora_sbmm(dz_ctx *ctx, const void *x_f16, const void *const *A_f16, const void *const *B_f16, int D,
                  int rank, const int32_t *token_to_adapter, void *out_f16, int T, int N, int K,
                  int accumulate, void *stream);
+
+/*
+ * Two variants of the compressed product, kept for the comparison the paper's compressed-matmul
+ * microbenchmark makes (Section 4.1: 2:4 sparsity on top of quantisation against quantisation alone
+ * at inputs of 1 .. 4096 rows) and for serving a single variant from a merged weight.
+ *
+ * Quantisation-only deltas (Section 4.1 step 3 without step 2): every column has a b-bit code,
+ *   value[n][k] = (codes[n][k] - zero[n][k / group]) * scale[n][k / group],
+ * codes u8 [N][K], scale / zero f16 [N][K / group] (all DEVICE).  dz_qpacked_bytes =
+ * N*K*bits/8 + 4*N*K/group.  dz_qpack_delta / dz_qunpack_delta are bit-exact inverses
+ * (dense_f32 [N][K], any output may be NULL); dz_qsbmm and dz_qlinear are dz_sbmm and dz_linear over
+ * blobs of this format (same arguments, shapes, index semantics and rounding).
+ */
+size_t dz_qpacked_bytes(int N, int K, int bits, int group);
+int dz_qpack_delta(dz_ctx *ctx, const uint8_t *codes, const void *scale_f16, const void *zero_f16, int N, int K,
+                   int bits, int group, void *packed_out, void *stream);
+int dz_qunpack_delta(dz_ctx *ctx, const void *packed, int N, int K, int bits, int group, uint8_t *codes,
+                     void *scale_f16, void *zero_f16, float *dense_f32, void *stream);
+int dz_qsbmm(dz_ctx *ctx, const void *x_f16, const void *const *qpacked_deltas, int D,
+             const int32_t *token_to_delta, void *out_f16, int T, int N, int K, int bits, int group,
+             int accumulate, void *stream);
+int dz_qlinear(dz_ctx *ctx, const void *x_f16, const void *W_f16, const void *const *qpacked_deltas, int D,
+               const int32_t *token_to_delta, void *out_f16, int T, int N, int K, int bits, int group,
+               void *stream);
+
+/*
+ * Merged weight of one variant (Section 5.1 Eq. (2) read right to left: W_base + delta is the variant's
+ * weight): merged[n][k] = f16(float(W[n][k]) + delta[n][k]) for a blob of dz_pack_delta, delta being its
+ * dequantised value (zero at the pruned columns).  W, packed, merged: DEVICE, 16-byte aligned;
+ * merged f16 [N][K], may not alias W.  dz_base_gemm on the result serves requests that all name this
+ * variant with one dense product; the extra rounding of W + delta to fp16 is part of that trade.
+ */
+int dz_merge_delta(dz_ctx *ctx, const void *W_f16, const void *packed, int N, int K, int bits, int group,
+                   void *merged_f16, void *stream);
 
 /*
  * Several linear layers that read the same x for the same requests -- the q, k, v projections of a

@@ -14,3 +14,4 @@ from . import c_oracle as c          # noqa: F401
 from . import np_oracle as np_       # noqa: F401
 from . import lora_oracle as lora    # noqa: F401   (low-rank adapters: Section 3.2, Section 6.4)
 from . import compress_oracle as compress_   # noqa: F401   (data-free 2:4 + RTN compressor: Section 4.1 steps 2-3)
+from . import quant_oracle as quant    # noqa: F401   (quantisation-only deltas, merged weights: Section 4.1 step 3, Section 5.1 Eq. (2))

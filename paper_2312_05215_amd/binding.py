@@ -9,7 +9,8 @@ import torch
 __all__ = [
     "DZ_OK", "DZ_ERR_ARG", "DZ_ERR_SHAPE", "DZ_ERR_BITS", "DZ_ERR_ALIGN", "DZ_ERR_HIP", "DZ_ERR_INDEX", "DZ_ERR_LIMIT",
     "DZ_OPT_SPLIT_K", "DZ_OPT_WORKGROUPS", "DZ_OPT_ROUND_TILES", "DZ_OPT_LARGE_BATCH_STREAMING", "DZ_OPT_WIDE_TILE",
-    "DZ_OPT_REUSE_SEGMENTS", "DZ_OPT_WG_SHAPE", "dz_set_option", "dz_linear_static", "dz_probe_read", "dz_probe_mfma", "dz_compress_delta", "dz_lora_sbmm",
+    "DZ_OPT_REUSE_SEGMENTS", "dz_set_option", "dz_linear_static", "dz_probe_read", "dz_probe_mfma", "dz_compress_delta", "dz_lora_sbmm",
+    "dz_qpacked_bytes", "dz_qpack_delta", "dz_qunpack_delta", "dz_qsbmm", "dz_qlinear", "dz_merge_delta",
     "DZ_MAX_DELTAS", "DzError", "lib", "lib_path", "dz_strerror", "dz_create", "dz_destroy",
     "dz_packed_bytes", "dz_pack_delta", "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm",
     "dz_linear", "dz_linear_group", "dz_check", "Context", "SYMBOLS", "DZ_MAX_GROUP",
@@ -18,12 +19,13 @@ __all__ = [
 
 DZ_OK, DZ_ERR_ARG, DZ_ERR_SHAPE, DZ_ERR_BITS, DZ_ERR_ALIGN, DZ_ERR_HIP, DZ_ERR_INDEX, DZ_ERR_LIMIT = 0, -1, -2, -3, -4, -5, -6, -7
 (DZ_OPT_SPLIT_K, DZ_OPT_WORKGROUPS, DZ_OPT_ROUND_TILES, DZ_OPT_LARGE_BATCH_STREAMING, DZ_OPT_WIDE_TILE,
- DZ_OPT_REUSE_SEGMENTS, DZ_OPT_WG_SHAPE) = 1, 2, 3, 4, 5, 6, 7
+ DZ_OPT_REUSE_SEGMENTS) = 1, 2, 3, 4, 5, 6
 DZ_MAX_DELTAS = 128
 DZ_MAX_GROUP = 4
 
 SYMBOLS = ["dz_strerror", "dz_last_hip_error", "dz_create", "dz_destroy", "dz_set_option", "dz_linear_static", "dz_probe_read", "dz_probe_mfma",
-           "dz_compress_delta", "dz_lora_sbmm", "dz_packed_bytes", "dz_pack_delta",
+           "dz_compress_delta", "dz_lora_sbmm", "dz_qpacked_bytes", "dz_qpack_delta", "dz_qunpack_delta", "dz_qsbmm",
+           "dz_qlinear", "dz_merge_delta", "dz_packed_bytes", "dz_pack_delta",
            "dz_unpack_delta", "dz_segment", "dz_base_gemm", "dz_sbmm", "dz_linear", "dz_linear_group", "dz_check",
            "dz_cache_create", "dz_cache_destroy", "dz_cache_acquire", "dz_cache_wait", "dz_cache_release",
            "dz_cache_stats"]
@@ -70,6 +72,13 @@ def lib() -> ctypes.CDLL:
                                       ctypes.POINTER(ci), ci, ci, ci, ci, vp]
         L.dz_check.argtypes = [vp, vp]
         L.dz_set_option.argtypes = [vp, ci, ci]
+        L.dz_qpacked_bytes.restype = ctypes.c_size_t
+        L.dz_qpacked_bytes.argtypes = [ci, ci, ci, ci]
+        L.dz_qpack_delta.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp]
+        L.dz_qunpack_delta.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp, vp]
+        L.dz_qsbmm.argtypes = [vp, vp, ctypes.POINTER(vp), ci, vp, vp, ci, ci, ci, ci, ci, ci, vp]
+        L.dz_qlinear.argtypes = [vp, vp, vp, ctypes.POINTER(vp), ci, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.dz_merge_delta.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
         L.dz_compress_delta.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp, vp]
         L.dz_lora_sbmm.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, ci, vp, vp, ci, ci, ci, ci, vp]
         L.dz_probe_read.argtypes = [vp, vp, ctypes.c_size_t, vp]
@@ -162,6 +171,40 @@ def dz_unpack_delta(ctx, packed, N, K, bits, group, codes=None, idx=None, scale=
     rc = lib().dz_unpack_delta(ctx, _ptr(packed), N, K, bits, group, _ptr(codes), _ptr(idx), _ptr(scale),
                                _ptr(zero), _ptr(dense_f32), _stream(stream))
     return _raise(ctx, rc, "dz_unpack_delta", check)
+
+
+def dz_qpacked_bytes(N: int, K: int, bits: int, group: int) -> int:
+    return int(lib().dz_qpacked_bytes(N, K, bits, group))
+
+
+def dz_qpack_delta(ctx, codes, scale, zero, N, K, bits, group, packed_out, stream=None, check=True) -> int:
+    rc = lib().dz_qpack_delta(ctx, _ptr(codes), _ptr(scale), _ptr(zero), N, K, bits, group, _ptr(packed_out), _stream(stream))
+    return _raise(ctx, rc, "dz_qpack_delta", check)
+
+
+def dz_qunpack_delta(ctx, packed, N, K, bits, group, codes=None, scale=None, zero=None, dense_f32=None, stream=None,
+                     check=True) -> int:
+    rc = lib().dz_qunpack_delta(ctx, _ptr(packed), N, K, bits, group, _ptr(codes), _ptr(scale), _ptr(zero), _ptr(dense_f32),
+                                _stream(stream))
+    return _raise(ctx, rc, "dz_qunpack_delta", check)
+
+
+def dz_qsbmm(ctx, x, qpacked_deltas, token_to_delta, out, T, N, K, bits, group, accumulate=0, stream=None, check=True) -> int:
+    arr, D = _ptr_array(qpacked_deltas)
+    rc = lib().dz_qsbmm(ctx, _ptr(x), arr, D, _ptr(token_to_delta), _ptr(out), T, N, K, bits, group, int(accumulate),
+                        _stream(stream))
+    return _raise(ctx, rc, "dz_qsbmm", check)
+
+
+def dz_qlinear(ctx, x, W, qpacked_deltas, token_to_delta, out, T, N, K, bits, group, stream=None, check=True) -> int:
+    arr, D = _ptr_array(qpacked_deltas)
+    rc = lib().dz_qlinear(ctx, _ptr(x), _ptr(W), arr, D, _ptr(token_to_delta), _ptr(out), T, N, K, bits, group, _stream(stream))
+    return _raise(ctx, rc, "dz_qlinear", check)
+
+
+def dz_merge_delta(ctx, W, packed, N, K, bits, group, merged_out, stream=None, check=True) -> int:
+    rc = lib().dz_merge_delta(ctx, _ptr(W), _ptr(packed), N, K, bits, group, _ptr(merged_out), _stream(stream))
+    return _raise(ctx, rc, "dz_merge_delta", check)
 
 
 def dz_compress_delta(ctx, delta, N, K, bits, group, codes, idx, scale, zero, stream=None, check=True) -> int:

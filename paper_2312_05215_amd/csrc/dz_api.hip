@@ -270,7 +270,7 @@ int dz_segment(dz_ctx *ctx, const int32_t *ids, int T, int D, int32_t *counts, i
 // kernel for all of them.  Large batches: the tiled kernel, one projection after the other.
 static int run_group(dz_ctx *ctx, const void *x, int P, const void *const *W, const void *const *deltas, int D,
                      const int32_t *ids, void *const *out, const int *N, int T, int K, int bits, int group,
-                     int accumulate, bool has_base, bool has_delta, hipStream_t st)
+                     int accumulate, bool has_base, bool has_delta, hipStream_t st, bool quant_only = false)
 {
     if (!ctx || T < 0 || D < 0 || D > DZ_MAX_DELTAS || P < 1 || P > DZ_MAX_GROUP || !N || !out) return DZ_ERR_ARG;
     if (has_base && !W) return DZ_ERR_ARG;
@@ -300,6 +300,7 @@ static int run_group(dz_ctx *ctx, const void *x, int P, const void *const *W, co
     a.has_base = has_base;
     // an SBMM with no deltas still runs (every request gets a zero delta term)
     a.has_delta = has_delta && (D > 0 || !has_base);
+    a.quant_only = quant_only ? 1 : 0;
     a.err_flag = ctx->err_flag;
     const bool tiled = T > 64 && !ctx->no_prefill;      // large batches: MFMA-bound tiled kernel
     if (has_delta && D > 0 && T <= 64) {
@@ -377,6 +378,61 @@ int dz_linear_group(dz_ctx *ctx, const void *x, int P, const void *const *W, con
                     void *stream)
 {
     return run_group(ctx, x, P, W, deltas, D, ids, out, N, T, K, bits, group, 0, true, true, (hipStream_t)stream);
+}
+
+size_t dz_qpacked_bytes(int N, int K, int bits, int group)
+{
+    if (check_shape(N, K, bits, group, true) != DZ_OK) return 0;
+    return (size_t)N * K * bits / 8 + (size_t)4 * N * K / group;
+}
+
+int dz_qpack_delta(dz_ctx *ctx, const uint8_t *codes, const void *scale, const void *zero, int N, int K, int bits,
+                   int group, void *packed, void *stream)
+{
+    if (!ctx || !codes || !scale || !zero || !packed) return DZ_ERR_ARG;
+    int rc = check_shape(N, K, bits, group, true);
+    if (rc) return rc;
+    if (!aligned16(packed) || (reinterpret_cast<uintptr_t>(scale) & 1) || (reinterpret_cast<uintptr_t>(zero) & 1))
+        return DZ_ERR_ALIGN;
+    DeviceGuard guard(ctx->device);
+    return dz_launch_qpack(ctx, codes, scale, zero, N, K, bits, group, packed, (hipStream_t)stream);
+}
+
+int dz_qunpack_delta(dz_ctx *ctx, const void *packed, int N, int K, int bits, int group, uint8_t *codes, void *scale,
+                     void *zero, float *dense, void *stream)
+{
+    if (!ctx || !packed) return DZ_ERR_ARG;
+    int rc = check_shape(N, K, bits, group, true);
+    if (rc) return rc;
+    if (!aligned16(packed) || (reinterpret_cast<uintptr_t>(scale) & 1) || (reinterpret_cast<uintptr_t>(zero) & 1) ||
+        (reinterpret_cast<uintptr_t>(dense) & 3))
+        return DZ_ERR_ALIGN;
+    DeviceGuard guard(ctx->device);
+    return dz_launch_qunpack(ctx, packed, N, K, bits, group, codes, scale, zero, dense, (hipStream_t)stream);
+}
+
+int dz_qsbmm(dz_ctx *ctx, const void *x, const void *const *deltas, int D, const int32_t *ids, void *out, int T, int N,
+             int K, int bits, int group, int accumulate, void *stream)
+{
+    return run_group(ctx, x, 1, nullptr, deltas, D, ids, &out, &N, T, K, bits, group, accumulate ? 1 : 0, false, true,
+                     (hipStream_t)stream, true);
+}
+
+int dz_qlinear(dz_ctx *ctx, const void *x, const void *W, const void *const *deltas, int D, const int32_t *ids, void *out,
+               int T, int N, int K, int bits, int group, void *stream)
+{
+    return run_group(ctx, x, 1, &W, deltas, D, ids, &out, &N, T, K, bits, group, 0, true, true, (hipStream_t)stream, true);
+}
+
+int dz_merge_delta(dz_ctx *ctx, const void *W, const void *packed, int N, int K, int bits, int group, void *merged,
+                   void *stream)
+{
+    if (!ctx || !W || !packed || !merged) return DZ_ERR_ARG;
+    int rc = check_shape(N, K, bits, group, true);
+    if (rc) return rc;
+    if (!aligned16(W) || !aligned16(packed) || !aligned16(merged)) return DZ_ERR_ALIGN;
+    DeviceGuard guard(ctx->device);
+    return dz_launch_merge(ctx, W, packed, N, K, bits, group, merged, (hipStream_t)stream);
 }
 
 int dz_compress_delta(dz_ctx *ctx, const void *delta, int N, int K, int bits, int group, uint8_t *codes, uint8_t *idx,
@@ -458,13 +514,6 @@ int dz_set_option(dz_ctx *ctx, int key, int value)
     case DZ_OPT_REUSE_SEGMENTS:
         ctx->reuse_segments = value ? 1 : 0;
         ctx->seg_ids = nullptr;
-        return DZ_OK;
-    case DZ_OPT_WG_SHAPE:
-        // waves x row tiles per wave of the streaming kernel: only the shapes that are built
-        if (value == 0) { ctx->wg_waves = ctx->wg_rtiles = 0; return DZ_OK; }
-        if (value != 81 && value != 82 && value != 42) return DZ_ERR_ARG;
-        ctx->wg_waves = value / 10;
-        ctx->wg_rtiles = value % 10;
         return DZ_OK;
     default: return DZ_ERR_ARG;
     }

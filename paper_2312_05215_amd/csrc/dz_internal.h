@@ -32,7 +32,6 @@ struct dz_ctx {
     int target_wgs = 0;             // DZ_OPT_WORKGROUPS
     int round_tiles = 0;            // DZ_OPT_ROUND_TILES
     int no_prefill = 0;             // DZ_OPT_LARGE_BATCH_STREAMING
-    int wg_waves = 0, wg_rtiles = 0; // DZ_OPT_WG_SHAPE: workgroup shape of the streaming kernel
     int num_cus = 0;                // compute units of the device
     int tile_kernel = 1;            // DZ_OPT_WIDE_TILE
     int reuse_segments = 0;         // DZ_OPT_REUSE_SEGMENTS
@@ -76,6 +75,7 @@ struct DzStreamArgs {
     int S;                      // streaming kernel: workgroups per chunk of 64 request rows; tiled kernel: k slices per tile
     int max_slots;              // most workgroups sharing one row block (partial-sum slots)
     int has_base, has_delta;
+    int quant_only;             // the packed deltas are in the quantisation-only format (no 2:4 pruning)
 };
 
 int dz_set_hip_error(dz_ctx *ctx, hipError_t e);
@@ -111,6 +111,11 @@ int dz_launch_stream(dz_ctx *, const DzStreamArgs &, const DzGroup &, const DzGr
 int dz_launch_prefill(dz_ctx *, const DzStreamArgs &, const DzDeltaPtrs &, hipStream_t);
 int dz_launch_tile(dz_ctx *, const DzStreamArgs &, hipStream_t);
 bool dz_tile_fits(const DzStreamArgs &);
+int dz_launch_qpack(dz_ctx *, const uint8_t *codes, const void *scale, const void *zero, int N, int K, int bits, int group,
+                    void *packed, hipStream_t);
+int dz_launch_qunpack(dz_ctx *, const void *packed, int N, int K, int bits, int group, uint8_t *codes, void *scale,
+                      void *zero, float *dense, hipStream_t);
+int dz_launch_merge(dz_ctx *, const void *W, const void *packed, int N, int K, int bits, int group, void *merged, hipStream_t);
 int dz_launch_compress(dz_ctx *, const void *delta, int N, int K, int bits, int group, uint8_t *codes, uint8_t *idx,
                        void *scale, void *zero, hipStream_t);
 int dz_launch_lora(dz_ctx *, const void *x, const void *const *A, const void *const *B, int D, int rank, const int32_t *ids,

@@ -56,6 +56,44 @@ DZ_HD DzLayout dz_make_layout(int N, int K, int bits, int group)
     return L;
 }
 
+// The quantisation-only format (no 2:4 pruning: a b-bit code for every column; Section 4.1 step 3
+// alone).  A dense group of four columns is the sum of two 2:4 patterns with fixed positions, columns
+// {0, 1} (half 0) and columns {2, 3} (half 1); each half of a tile is stored exactly like plane C of
+// a 2:4 tile whose kept columns are those two, so the sparse MFMA multiplies it with a constant
+// position word and no positions are stored:
+//   4-bit:  tile at ti*2048: half h at +1024h + 16*l : uint4, dword s = codes of step s
+//   2-bit:  tile at ti*1024 + 16*l : uint4 {half 0: c01, c23, half 1: c01, c23}
+//   scales: plane S as above, after all tiles
+DZ_HD DzLayout dz_make_qlayout(int N, int K, int bits, int group)
+{
+    DzLayout L;
+    L.N = N; L.K = K; L.bits = bits; L.group = group;
+    L.RT = N / 16; L.KT = K / 256; L.GPT = 256 / group;
+    size_t tiles = (size_t)L.RT * L.KT;
+    L.off_idx = 0;
+    L.off_scale = tiles * (bits == 4 ? 2048 : 1024);
+    L.total = L.off_scale + tiles * 16 * (size_t)L.GPT * 4;
+    return L;
+}
+
+// dword index and bit shift of the code of (row n, column k) in a quantisation-only blob
+DZ_HD size_t dz_qcode_dword(const DzLayout &L, int n, int k)
+{
+    int kt = k >> 8, kin = k & 255;
+    int s = kin >> 6, q = (kin & 63) >> 4, h = (kin & 3) >> 1;
+    size_t tile = (size_t)(n >> 4) * L.KT + kt;
+    int lane = q * 16 + (n & 15);
+    if (L.bits == 4) return (tile * 2048 + (size_t)h * 1024 + (size_t)lane * 16) / 4 + s;
+    return (tile * 1024 + (size_t)lane * 16) / 4 + 2 * h + (s >> 1);
+}
+DZ_HD int dz_qcode_shift(const DzLayout &L, int k)
+{
+    int kin = k & 255;
+    int s = kin >> 6, j = (kin & 15) >> 2, hh = kin & 1;
+    if (L.bits == 4) return 16 * hh + 4 * j;
+    return 16 * hh + 8 * (s & 1) + 2 * j;
+}
+
 // Where kept entry (row n, kept column kk in [0, K/2)) lives.
 struct DzSlot {
     size_t tile; int lane; int step; int e;     // e = kept slot 0..7 inside the lane's step

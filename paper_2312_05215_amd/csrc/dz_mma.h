@@ -109,22 +109,6 @@ __device__ __forceinline__ h8 as_h8(uint32_t a, uint32_t b, uint32_t c, uint32_t
     return __builtin_bit_cast(h8, (u4){a, b, c, d});
 }
 
-// Inside one LDS round (a slice of k whose x rows sit in LDS) a wave first streams its rows of W
-// (base phase), then the packed tiles of every delta that has requests (delta phase).  Both phases
-// are software pipelines over fixed-size loads held in named register buffers:
-//   base step  : 2 x 16 bytes of W per lane and row tile  -> two dense MFMAs per column block
-//   delta task : one packed tile (16 rows x 256 k)         -> four sparse MFMAs per column block
-// Loads go through buffer instructions: a wave-uniform resource (base pointer + size in bytes,
-// bounds-checked by the hardware), a wave-uniform byte offset in an SGPR and a per-lane byte
-// offset that never changes.  No branch surrounds a streaming load, so the hardware load counter
-// the compiler waits on is exact and the prefetched loads really stay in flight.
-template <int BITS, int GROUP>
-struct Fmt {
-    static constexpr int GPT = 256 / GROUP;                         // quantisation groups per tile row
-    static constexpr int SC0 = (BITS == 4) ? 6 : 4;                 // first scale dword in a stage
-    static constexpr int SD = SC0 + GPT;                            // dwords per lane and row tile
-};
-
 struct LaneOffs {
     uint32_t w;         // row * K * 2 + q * 16      (W fragment of a base step)
     uint32_t c;         // lane * 16                 (packed codes)
@@ -139,6 +123,73 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
+
+// Inside one LDS round (a slice of k whose x rows sit in LDS) a wave first streams its rows of W
+// (base phase), then the packed tiles of every delta that has requests (delta phase).  Both phases
+// are software pipelines over fixed-size loads held in named register buffers:
+//   base step  : 2 x 16 bytes of W per lane and row tile  -> two dense MFMAs per column block
+//   delta task : one packed tile (16 rows x 256 k)         -> four sparse MFMAs per column block
+// Loads go through buffer instructions: a wave-uniform resource (base pointer + size in bytes,
+// bounds-checked by the hardware), a wave-uniform byte offset in an SGPR and a per-lane byte
+// offset that never changes.  No branch surrounds a streaming load, so the hardware load counter
+// the compiler waits on is exact and the prefetched loads really stay in flight.
+//
+// QO selects the quantisation-only format (no 2:4 pruning, a code for every column).  A dense group
+// of four is the sum of two 2:4 patterns with fixed positions -- columns {0, 1} and columns {2, 3}
+// -- so a quantisation-only tile is stored as two such halves and multiplied by the same sparse
+// MFMAs with constant position words: the kernels differ only in what a tile's loads fetch and in
+// running the four steps twice.
+template <int BITS, int GROUP, bool QO = false>
+struct Fmt {
+    static constexpr int GPT = 256 / GROUP;                         // quantisation groups per tile row
+    static constexpr int NH = QO ? 2 : 1;                           // 2:4 halves per tile
+    static constexpr int SC0 = QO ? ((BITS == 4) ? 8 : 4) : ((BITS == 4) ? 6 : 4);   // first scale dword in a stage
+    static constexpr int SD = SC0 + GPT;                            // dwords per lane and row tile
+    static constexpr uint32_t TILE_BYTES = (QO && BITS == 4) ? 2048u : 1024u;   // plane C bytes per tile
+};
+
+// The codes of step s of half h of a lane's stage registers (shifted as dequant_step wants them)
+// and the dword that carries the step's positions.
+template <int BITS, bool QO>
+__device__ __forceinline__ uint32_t step_codes(const uint32_t *st, int s, int h, uint32_t &idxw)
+{
+    if constexpr (QO) {
+        idxw = h ? 0xEEEEEEEEu : 0x44444444u;       // every group keeps columns (2, 3) / (0, 1)
+        if (BITS == 4) return st[4 * h + s];
+        return st[2 * h + (s >> 1)] >> (8 * (s & 1));
+    } else {
+        if (BITS == 4) { idxw = st[4 + (s >> 1)]; return st[s]; }
+        idxw = st[2 + (s >> 1)];
+        return st[s >> 1] >> (8 * (s & 1));
+    }
+}
+
+// The loads of one packed tile for one row tile into its stage registers.
+template <int BITS, int GROUP, bool QO>
+__device__ __forceinline__ void tile_loads(__amdgpu_buffer_rsrc_t rs, uint32_t tile, const LaneOffs &lo, uint32_t off_idx,
+                                           uint32_t off_scale, uint32_t (&st)[Fmt<BITS, GROUP, QO>::SD])
+{
+    typedef Fmt<BITS, GROUP, QO> F;
+    const uint32_t sc = off_scale + tile * (16u * F::GPT * 4u);
+    const u32x4 x0 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.c, tile * F::TILE_BYTES, 0);
+    st[0] = x0.x; st[1] = x0.y; st[2] = x0.z; st[3] = x0.w;
+    if constexpr (QO && BITS == 4) {
+        const u32x4 x1 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.c, tile * F::TILE_BYTES + 1024u, 0);
+        st[4] = x1.x; st[5] = x1.y; st[6] = x1.z; st[7] = x1.w;
+    }
+    if constexpr (!QO && BITS == 4) {
+        const u32x2 x1 = __builtin_amdgcn_raw_buffer_load_b64(rs, lo.i, off_idx + tile * 512u, 0);
+        st[4] = x1.x; st[5] = x1.y;
+    }
+    if constexpr (F::GPT == 2) {
+        const u32x2 x2 = __builtin_amdgcn_raw_buffer_load_b64(rs, lo.s, sc, 0);
+        st[F::SC0] = x2.x; st[F::SC0 + 1] = x2.y;
+    } else {
+        const u32x4 x2 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.s, sc, 0);
+        st[F::SC0] = x2.x; st[F::SC0 + 1] = x2.y; st[F::SC0 + 2] = x2.z; st[F::SC0 + 3] = x2.w;
+    }
+}
+
 
 // ------------------------------------------------------------------------------------ base phase
 // One step = 64 k of W for R row tiles.  step index s counts from the start of the round.
@@ -177,13 +228,12 @@ struct Cursor {
     int seg;        // segment number
 };
 
-template <int BITS, int GROUP, int R>
+template <int BITS, int GROUP, bool QO, int R>
 __device__ __forceinline__ void delta_issue(const Cursor &c, bool valid, const Geo &g, const int (&rtc)[R], const LaneOffs &lo,
                                             const unsigned long long *s_dptr, const int *s_seg_delta,
                                             uint32_t off_idx, uint32_t off_scale, uint32_t blob_bytes,
-                                            uint32_t (&st)[R][Fmt<BITS, GROUP>::SD])
+                                            uint32_t (&st)[R][Fmt<BITS, GROUP, QO>::SD])
 {
-    typedef Fmt<BITS, GROUP> F;
     // With no delta task in this round the loads are still issued (so the load count never
     // depends on a branch) but against an empty resource: the hardware returns zeros and touches
     // no memory.
@@ -192,23 +242,8 @@ __device__ __forceinline__ void delta_issue(const Cursor &c, bool valid, const G
     const uint32_t h = __builtin_amdgcn_readfirstlane((uint32_t)(bp >> 32));
     const __amdgpu_buffer_rsrc_t rs = make_rsrc((const void *)(((unsigned long long)h << 32) | l), valid ? blob_bytes : 0u);
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const uint32_t tile = (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)c.kt;
-        const uint32_t sc = off_scale + tile * (16u * F::GPT * 4u);
-        const u32x4 x0 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.c, tile * 1024u, 0);
-        st[r][0] = x0.x; st[r][1] = x0.y; st[r][2] = x0.z; st[r][3] = x0.w;
-        if constexpr (BITS == 4) {
-            const u32x2 x1 = __builtin_amdgcn_raw_buffer_load_b64(rs, lo.i, off_idx + tile * 512u, 0);
-            st[r][4] = x1.x; st[r][5] = x1.y;
-        }
-        if constexpr (F::GPT == 2) {
-            const u32x2 x2 = __builtin_amdgcn_raw_buffer_load_b64(rs, lo.s, sc, 0);
-            st[r][F::SC0] = x2.x; st[r][F::SC0 + 1] = x2.y;
-        } else {
-            const u32x4 x2 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.s, sc, 0);
-            st[r][F::SC0] = x2.x; st[r][F::SC0 + 1] = x2.y; st[r][F::SC0 + 2] = x2.z; st[r][F::SC0 + 3] = x2.w;
-        }
-    }
+    for (int r = 0; r < R; ++r)
+        tile_loads<BITS, GROUP, QO>(rs, (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)c.kt, lo, off_idx, off_scale, st[r]);
 }
 
 __device__ __forceinline__ void advance(Cursor &c, int kr0, int kr1)

@@ -122,6 +122,80 @@ __global__ void unpack_scale_kernel(DzLayout L, const uint32_t *__restrict__ blo
     if (zero) zero[i] = (uint16_t)(sz >> 16);
 }
 
+// ---- quantisation-only format: one thread per dword of codes (pack) or per column (unpack)
+__global__ void qpack_codes_kernel(DzLayout L, const uint8_t *__restrict__ codes, uint32_t *__restrict__ out)
+{
+    const int per_dword = 32 / L.bits;                  // 8 or 16 codes
+    const size_t total = (size_t)L.N * L.K / per_dword;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    // dword i of plane C: find (tile, half, lane, dword-in-lane), then gather its codes
+    const size_t tile_dwords = (L.bits == 4) ? 512 : 256;
+    const size_t tile = i / tile_dwords;
+    const int r = (int)(i % tile_dwords);
+    int h, lane, d;
+    if (L.bits == 4) { h = r / 256; lane = (r % 256) / 4; d = r % 4; }
+    else { lane = r / 4; d = r % 4; h = d >> 1; }
+    const int rt = (int)(tile / L.KT), kt = (int)(tile % L.KT);
+    const int n = rt * 16 + (lane & 15), q = lane >> 4;
+    const uint8_t *row = codes + (size_t)n * L.K;
+    const uint32_t mask = (1u << L.bits) - 1u;
+    uint32_t w = 0;
+    const int nsteps = (L.bits == 4) ? 1 : 2;
+    for (int ss = 0; ss < nsteps; ++ss) {
+        const int step = (L.bits == 4) ? d : 2 * (d & 1) + ss;
+        const int k0 = kt * 256 + step * 64 + q * 16;   // first column of this lane's step
+        for (int j = 0; j < 4; ++j)
+            for (int hh = 0; hh < 2; ++hh) {
+                const uint32_t c = row[k0 + 4 * j + 2 * h + hh] & mask;
+                w |= c << ((L.bits == 4) ? 16 * hh + 4 * j : 16 * hh + 8 * ss + 2 * j);
+            }
+    }
+    out[i] = w;
+}
+
+__global__ void qunpack_kernel(DzLayout L, const uint32_t *__restrict__ blob, uint8_t *__restrict__ codes,
+                               float *__restrict__ dense)
+{
+    const size_t total = (size_t)L.N * L.K;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int n = (int)(i / L.K), k = (int)(i % L.K);
+    const uint32_t c = (blob[dz_qcode_dword(L, n, k)] >> dz_qcode_shift(L, k)) & ((1u << L.bits) - 1u);
+    if (codes) codes[i] = (uint8_t)c;
+    if (dense) {
+        const uint32_t sz = blob[dz_scale_dword(L, n, k / L.group)];
+        dense[i] = ((float)c - half_bits_to_float((uint16_t)(sz >> 16))) * half_bits_to_float((uint16_t)(sz & 0xffff));
+    }
+}
+
+// merged[n][k] = f16( float(W[n][k]) + (code - zero) * scale at the kept columns ): one thread per
+// group of four columns of a 2:4 blob
+__global__ void merge_kernel(DzLayout L, const _Float16 *__restrict__ W, const uint32_t *__restrict__ blob,
+                             _Float16 *__restrict__ merged)
+{
+    const int g4n = L.K / 4;
+    size_t total = (size_t)L.N * g4n;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int n = (int)(i / g4n), g4 = (int)(i % g4n);
+    const uint32_t mask = (1u << L.bits) - 1u;
+    const uint32_t sz = blob[dz_scale_dword(L, n, (4 * g4) / L.group)];
+    const float s = half_bits_to_float((uint16_t)(sz & 0xffff)), z = half_bits_to_float((uint16_t)(sz >> 16));
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    const h4 w = *(const h4 *)(W + (size_t)n * L.K + 4 * (size_t)g4);
+    float v[4] = {(float)w.x, (float)w.y, (float)w.z, (float)w.w};
+    for (int j = 0; j < 2; ++j) {
+        const DzSlot sl = dz_slot_of(L, n, 2 * g4 + j);
+        const uint32_t c = (blob[dz_code_dword(L, sl)] >> dz_code_shift(L, sl)) & mask;
+        const uint32_t p = (blob[dz_idx_dword(L, sl)] >> dz_idx_shift(sl)) & 3u;
+        const float d = ((float)c - z) * s;
+#pragma unroll
+        for (uint32_t pos = 0; pos < 4; ++pos) v[pos] += (p == pos) ? d : 0.f;
+    }
+    *(h4 *)(merged + (size_t)n * L.K + 4 * (size_t)g4) = (h4){(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+}
+
 inline unsigned blocks_for(size_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
 
 }  // namespace
@@ -152,5 +226,40 @@ int dz_launch_unpack(dz_ctx *ctx, const void *packed, int N, int K, int bits, in
     if (scale || zero)
         hipLaunchKernelGGL(unpack_scale_kernel, dim3(blocks_for((size_t)N * (K / group), bs)), dim3(bs), 0, st,
                            L, (const uint32_t *)packed, (uint16_t *)scale, (uint16_t *)zero);
+    return dz_set_hip_error(ctx, hipGetLastError());
+}
+
+int dz_launch_qpack(dz_ctx *ctx, const uint8_t *codes, const void *scale, const void *zero, int N, int K, int bits,
+                    int group, void *packed, hipStream_t st)
+{
+    DzLayout L = dz_make_qlayout(N, K, bits, group);
+    const int bs = 256;
+    hipLaunchKernelGGL(qpack_codes_kernel, dim3(blocks_for((size_t)N * K * bits / 32, bs)), dim3(bs), 0, st, L, codes,
+                       (uint32_t *)packed);
+    hipLaunchKernelGGL(pack_scale_kernel, dim3(blocks_for((size_t)N * (K / group), bs)), dim3(bs), 0, st, L,
+                       (const uint16_t *)scale, (const uint16_t *)zero, (uint32_t *)packed);
+    return dz_set_hip_error(ctx, hipGetLastError());
+}
+
+int dz_launch_qunpack(dz_ctx *ctx, const void *packed, int N, int K, int bits, int group, uint8_t *codes, void *scale,
+                      void *zero, float *dense, hipStream_t st)
+{
+    DzLayout L = dz_make_qlayout(N, K, bits, group);
+    const int bs = 256;
+    if (codes || dense)
+        hipLaunchKernelGGL(qunpack_kernel, dim3(blocks_for((size_t)N * K, bs)), dim3(bs), 0, st, L, (const uint32_t *)packed,
+                           codes, dense);
+    if (scale || zero)
+        hipLaunchKernelGGL(unpack_scale_kernel, dim3(blocks_for((size_t)N * (K / group), bs)), dim3(bs), 0, st, L,
+                           (const uint32_t *)packed, (uint16_t *)scale, (uint16_t *)zero);
+    return dz_set_hip_error(ctx, hipGetLastError());
+}
+
+int dz_launch_merge(dz_ctx *ctx, const void *W, const void *packed, int N, int K, int bits, int group, void *merged,
+                    hipStream_t st)
+{
+    DzLayout L = dz_make_layout(N, K, bits, group);
+    hipLaunchKernelGGL(merge_kernel, dim3(blocks_for((size_t)N * (K / 4), 256)), dim3(256), 0, st, L, (const _Float16 *)W,
+                       (const uint32_t *)packed, (_Float16 *)merged);
     return dz_set_hip_error(ctx, hipGetLastError());
 }

@@ -63,8 +63,8 @@ __device__ __forceinline__ void base_step(const u32x4 (&buf)[R][2], const _Float
 // One step of a tile whose request rows all belong to one delta: the B fragment a column block
 // reads for the base product also feeds the sparse MFMA of the delta (av: the step's dequantised
 // kept values, idxw: their positions, ODD: which half of idxw the step uses).
-template <int R, int J, bool NEXT, int ODD>
-__device__ __forceinline__ void fused_step(const u32x4 (&buf)[R][2], const h8 (&av)[R], const uint32_t (&idxw)[R],
+template <int R, int J, bool NEXT, int ODD, int NH>
+__device__ __forceinline__ void fused_step(const u32x4 (&buf)[R][2], const h8 (&av)[NH][R], const uint32_t (&idxw)[NH][R],
                                            const _Float16 *xs, const Geo &g, const int (&brow)[J], int kofs,
                                            f4 (&acc)[R][J], h16 (&bq)[PFB])
 {
@@ -81,35 +81,35 @@ __device__ __forceinline__ void fused_step(const u32x4 (&buf)[R][2], const h8 (&
             acc[r][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, buf[r][1]), b1, acc[r][j], 0, 0, 0);
         }
 #pragma unroll
-        for (int r = 0; r < R; ++r) acc[r][j] = smfmac<ODD>(av[r], b, acc[r][j], (int)idxw[r]);
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[r][j] = smfmac<ODD>(av[h][r], b, acc[r][j], (int)idxw[h][r]);
         __builtin_amdgcn_sched_barrier(0);      // keep the reads two blocks ahead of their MFMAs
     }
 }
 
-// Dequantised kept values and positions of step s of a packed tile held in stage registers.
-template <int BITS, int GROUP, int R>
-__device__ __forceinline__ void step_dequant(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], int s, h8 (&av)[R],
+// Dequantised kept values and positions of step s (half h) of a packed tile held in stage registers.
+template <int BITS, int GROUP, bool QO, int R>
+__device__ __forceinline__ void step_dequant(const uint32_t (&st)[R][Fmt<BITS, GROUP, QO>::SD], int s, int h, h8 (&av)[R],
                                              uint32_t (&idxw)[R])
 {
-    typedef Fmt<BITS, GROUP> F;
+    typedef Fmt<BITS, GROUP, QO> F;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const h2 sz2 = as_h2(st[r][F::SC0 + s * F::GPT / 4]);
         const h2 s2 = (h2){sz2.x, sz2.x};
         const h2 z2 = (h2){sz2.y, sz2.y};
-        uint32_t w;
-        if (BITS == 4) { w = st[r][s]; idxw[r] = st[r][4 + (s >> 1)]; }
-        else { w = st[r][s >> 1] >> (8 * (s & 1)); idxw[r] = st[r][2 + (s >> 1)]; }
+        const uint32_t w = step_codes<BITS, QO>(st[r], s, h, idxw[r]);
         av[r] = dequant_step<BITS>(w, s2, z2);
     }
 }
 
-// Packed tile (16 rows x 256 k) of R row tiles -> MFMA A operands of the four steps.
-template <int BITS, int GROUP, int R>
-__device__ __forceinline__ void delta_dequant(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], h8 (&av)[4][R],
+// Packed tile (16 rows x 256 k; half h of it) of R row tiles -> MFMA A operands of the four steps.
+template <int BITS, int GROUP, bool QO, int R>
+__device__ __forceinline__ void delta_dequant(const uint32_t (&st)[R][Fmt<BITS, GROUP, QO>::SD], int h, h8 (&av)[4][R],
                                               uint32_t (&idxw)[2][R])
 {
-    typedef Fmt<BITS, GROUP> F;
+    typedef Fmt<BITS, GROUP, QO> F;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
 #pragma unroll
@@ -117,13 +117,9 @@ __device__ __forceinline__ void delta_dequant(const uint32_t (&st)[R][Fmt<BITS, 
             const h2 sz2 = as_h2(st[r][F::SC0 + s * F::GPT / 4]);
             const h2 s2 = (h2){sz2.x, sz2.x};
             const h2 z2 = (h2){sz2.y, sz2.y};
-            uint32_t w;
-            if (BITS == 4) w = st[r][s];
-            else w = st[r][s >> 1] >> (8 * (s & 1));
+            const uint32_t w = step_codes<BITS, QO>(st[r], s, h, idxw[s >> 1][r]);
             av[s][r] = dequant_step<BITS>(w, s2, z2);
         }
-        idxw[0][r] = st[r][(BITS == 4 ? 4 : 2)];
-        idxw[1][r] = st[r][(BITS == 4 ? 4 : 2) + 1];
     }
 }
 
@@ -163,11 +159,11 @@ __device__ __forceinline__ void delta_mm(const h8 (&av)[4][R], const uint32_t (&
     }
 }
 
-template <int BITS, int GROUP, int PW, int PR, int PJ, bool HAS_BASE, bool HAS_DELTA>
+template <int BITS, int GROUP, bool QO, int PW, int PR, int PJ, bool HAS_BASE, bool HAS_DELTA>
 __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDeltaPtrs dp, int NRB, int nchunks,
                                                           size_t off_idx, size_t off_scale, size_t blob_total)
 {
-    typedef Fmt<BITS, GROUP> F;
+    typedef Fmt<BITS, GROUP, QO> F;
     constexpr int SD = F::SD;
     constexpr int THREADS = PW * 64;
     constexpr int PCH = 16 * PJ;            // request rows per workgroup tile
@@ -341,7 +337,7 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     int cs = 0;                      // interleaved order: the step the fetch cursor is at
 #define PF_DISSUE(buf)                                                                                             \
     do {                                                                                                           \
-        delta_issue<BITS, GROUP, PR>(ci, ti < ndelta, g, rtc, lo, s_dptr, s_seg_delta, (uint32_t)off_idx,          \
+        delta_issue<BITS, GROUP, QO, PR>(ci, ti < ndelta, g, rtc, lo, s_dptr, s_seg_delta, (uint32_t)off_idx,          \
                                      (uint32_t)off_scale, blob_bytes, buf);                                        \
         ++ti;                                                                                                      \
         if constexpr (ILV) {                                                                                       \
@@ -375,15 +371,15 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
         PF_XLOAD(xnxtv, (st_) < 3 ? ktn : ktnn, ((st_) + 1) & 3);                                                  \
         base_issue<PR>(rw, wrow, lo.w, min(kt * 4 + (st_) + DIST, last_step), nxt);                                \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
-        h8 av[PR];                                                                                                 \
-        uint32_t idxw[PR];                                                                                         \
-        step_dequant<BITS, GROUP, PR>(st0, st_, av, idxw);                                                         \
+        h8 av[F::NH][PR];                                                                                          \
+        uint32_t idxw[F::NH][PR];                                                                                  \
+        _Pragma("unroll") for (int h = 0; h < F::NH; ++h) step_dequant<BITS, GROUP, QO, PR>(st0, st_, h, av[h], idxw[h]); \
         if ((st_) == 3) {       /* the stage registers are free: request the next k tile's packed tile */          \
             __builtin_amdgcn_sched_barrier(0);                                                                     \
             PF_DISSUE(st0);                                                                                        \
         }                                                                                                          \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
-        fused_step<PR, PJ, ((st_) < 3), ((st_) & 1)>(cur, av, idxw, xcur, g, brow, (st_) * 64, acc, bq);           \
+        fused_step<PR, PJ, ((st_) < 3), ((st_) & 1), F::NH>(cur, av, idxw, xcur, g, brow, (st_) * 64, acc, bq);    \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
         PF_XSTORE(xcurv, xnxt, st_);                                                                               \
         __builtin_amdgcn_sched_barrier(0);                                                                         \
@@ -411,15 +407,17 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
         // freed stage buffer, multiply
 #define PF_DSEG(buf, sg_)                                                                                          \
     do {                                                                                                           \
-        h8 av[4][PR];                                                                                              \
-        uint32_t idxw[2][PR];                                                                                      \
-        delta_dequant<BITS, GROUP, PR>(buf, av, idxw);                                                             \
-        __builtin_amdgcn_sched_barrier(0);                                                                         \
-        PF_DISSUE(buf);                                                                                            \
-        __builtin_amdgcn_sched_barrier(0);                                                                         \
         const int sb = __builtin_amdgcn_readfirstlane(s_seg_begin[sg_]);                                           \
         const int se = __builtin_amdgcn_readfirstlane(s_seg_begin[(sg_) + 1]);                                     \
-        delta_mm<PR, PJ>(av, idxw, xcur, PLDW, (int)(xs_all + zoff - xcur), g, sb, se, acc);                       \
+        _Pragma("unroll") for (int h = 0; h < F::NH; ++h) {                                                       \
+            h8 av[4][PR];                                                                                          \
+            uint32_t idxw[2][PR];                                                                                  \
+            delta_dequant<BITS, GROUP, QO, PR>(buf, h, av, idxw);                                                  \
+            __builtin_amdgcn_sched_barrier(0);                                                                     \
+            if (h == F::NH - 1) PF_DISSUE(buf);     /* the stage registers are free for the next tile */           \
+            __builtin_amdgcn_sched_barrier(0);                                                                     \
+            delta_mm<PR, PJ>(av, idxw, xcur, PLDW, (int)(xs_all + zoff - xcur), g, sb, se, acc);                   \
+        }                                                                                                          \
     } while (0)
 #define PF_BSTEP(st_, cur, nxt, xcurv, xnxtv)                                                                      \
     do {                                                                                                           \
@@ -518,10 +516,10 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     }
 }
 
-template <int BITS, int GROUP, int PW, int PR, int PJ, bool HB, bool HD>
+template <int BITS, int GROUP, bool QO, int PW, int PR, int PJ, bool HB, bool HD>
 hipError_t launch_pf(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int nchunks, const DzLayout &L, hipStream_t st)
 {
-    auto k = prefill_kernel<BITS, GROUP, PW, PR, PJ, HB, HD>;
+    auto k = prefill_kernel<BITS, GROUP, QO, PW, PR, PJ, HB, HD>;
     const size_t lds = (size_t)(2 * 16 * PJ + 1) * PLDW * sizeof(_Float16);
     static unsigned long long lds_allowed = 0;      // per instantiation
     const hipError_t e = dz_allow_lds((const void *)k, (int)lds, lds_allowed);
@@ -532,13 +530,14 @@ hipError_t launch_pf(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int 
     return hipGetLastError();
 }
 
-template <int PW, int PR, int PJ, bool HB, bool HD>
+template <bool QO, int PW, int PR, int PJ, bool HB, bool HD>
 hipError_t launch_pf_fmt(const DzStreamArgs &a, const DzDeltaPtrs &dp, int NRB, int nchunks, const DzLayout &L, hipStream_t st)
 {
-    if (!HD || (a.bits == 4 && a.group == 128)) return launch_pf<4, 128, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
-    if (a.bits == 4) return launch_pf<4, 64, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
-    if (a.group == 128) return launch_pf<2, 128, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
-    return launch_pf<2, 64, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
+    if (!HD) return launch_pf<4, 128, false, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
+    if (a.bits == 4 && a.group == 128) return launch_pf<4, 128, QO, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
+    if (a.bits == 4) return launch_pf<4, 64, QO, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
+    if (a.group == 128) return launch_pf<2, 128, QO, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
+    return launch_pf<2, 64, QO, PW, PR, PJ, HB, HD>(a, dp, NRB, nchunks, L, st);
 }
 
 template <int PW, int PR, int PJ>
@@ -578,9 +577,13 @@ hipError_t launch_pf_kind(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPt
     }
     a.partial = ctx->partial;
     a.counters = ctx->counters;
-    if (a.has_base && a.has_delta) return launch_pf_fmt<PW, PR, PJ, true, true>(a, dp, NRB, nchunks, L, st);
-    if (a.has_base) return launch_pf_fmt<PW, PR, PJ, true, false>(a, dp, NRB, nchunks, L, st);
-    return launch_pf_fmt<PW, PR, PJ, false, true>(a, dp, NRB, nchunks, L, st);
+    if (a.has_delta && a.quant_only) {
+        if (a.has_base) return launch_pf_fmt<true, PW, PR, PJ, true, true>(a, dp, NRB, nchunks, L, st);
+        return launch_pf_fmt<true, PW, PR, PJ, false, true>(a, dp, NRB, nchunks, L, st);
+    }
+    if (a.has_base && a.has_delta) return launch_pf_fmt<false, PW, PR, PJ, true, true>(a, dp, NRB, nchunks, L, st);
+    if (a.has_base) return launch_pf_fmt<false, PW, PR, PJ, true, false>(a, dp, NRB, nchunks, L, st);
+    return launch_pf_fmt<false, PW, PR, PJ, false, true>(a, dp, NRB, nchunks, L, st);
 }
 
 }  // namespace
@@ -598,12 +601,12 @@ int dz_launch_prefill(dz_ctx *ctx, const DzStreamArgs &args, const DzDeltaPtrs &
         const int cus = ctx->num_cus > 0 ? ctx->num_cus : 256;
         if (ctx->tile_kernel > 1 || wide_tiles * 10 >= (long long)cus * 3) return dz_launch_tile(ctx, a, st);
     }
-    DzLayout L = dz_make_layout(a.N, a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
+    DzLayout L = (a.has_delta && a.quant_only) ? dz_make_qlayout(a.N, a.K, a.bits, a.group)
+                                               : dz_make_layout(a.N, a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
     hipError_t e;
     int rc = DZ_OK;
     // 8 waves x 2 row tiles measured faster than 4 x 4 (two waves per SIMD hide each other's waits)
-    if (ctx->wg_waves == 4) e = launch_pf_kind<4, 4, 8>(ctx, a, dp, L, st, &rc);
-    else e = launch_pf_kind<8, 2, 8>(ctx, a, dp, L, st, &rc);
+    e = launch_pf_kind<8, 2, 8>(ctx, a, dp, L, st, &rc);
     if (rc != DZ_OK) return rc;
     return dz_set_hip_error(ctx, e);
 }

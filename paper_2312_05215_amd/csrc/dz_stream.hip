@@ -62,36 +62,20 @@ __device__ __forceinline__ void load_window_frags(const _Float16 *xs, const int 
         for (int j = 0; j < JW; ++j) bf[s][j] = load_b(xs, brow[J0 + j], g, kofs + s * 64);
 }
 
-template <int BITS, int GROUP, int R>
+template <int BITS, int GROUP, bool QO, int R>
 __device__ __forceinline__ void stream_delta_issue(const Cursor &c, bool valid, const Geo &g, const int (&rtc)[R],
                                                    const LaneOffs &lo, const SegTable &tab, uint32_t off_idx,
                                                    uint32_t off_scale, uint32_t blob_bytes,
-                                                   uint32_t (&st)[R][Fmt<BITS, GROUP>::SD])
+                                                   uint32_t (&st)[R][Fmt<BITS, GROUP, QO>::SD])
 {
-    typedef Fmt<BITS, GROUP> F;
     // With no task left the loads are still issued (so the load count never depends on a branch)
     // but against an empty resource: the hardware returns zeros and touches no memory.
     const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)tab.plo, c.seg);
     const uint32_t h = (uint32_t)__builtin_amdgcn_readlane((int)tab.phi, c.seg);
     const __amdgpu_buffer_rsrc_t rs = make_rsrc((const void *)(((unsigned long long)h << 32) | l), valid ? blob_bytes : 0u);
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const uint32_t tile = (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)c.kt;
-        const uint32_t sc = off_scale + tile * (16u * F::GPT * 4u);
-        const u32x4 x0 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.c, tile * 1024u, 0);
-        st[r][0] = x0.x; st[r][1] = x0.y; st[r][2] = x0.z; st[r][3] = x0.w;
-        if constexpr (BITS == 4) {
-            const u32x2 x1 = __builtin_amdgcn_raw_buffer_load_b64(rs, lo.i, off_idx + tile * 512u, 0);
-            st[r][4] = x1.x; st[r][5] = x1.y;
-        }
-        if constexpr (F::GPT == 2) {
-            const u32x2 x2 = __builtin_amdgcn_raw_buffer_load_b64(rs, lo.s, sc, 0);
-            st[r][F::SC0] = x2.x; st[r][F::SC0 + 1] = x2.y;
-        } else {
-            const u32x4 x2 = __builtin_amdgcn_raw_buffer_load_b128(rs, lo.s, sc, 0);
-            st[r][F::SC0] = x2.x; st[r][F::SC0 + 1] = x2.y; st[r][F::SC0 + 2] = x2.z; st[r][F::SC0 + 3] = x2.w;
-        }
-    }
+    for (int r = 0; r < R; ++r)
+        tile_loads<BITS, GROUP, QO>(rs, (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)c.kt, lo, off_idx, off_scale, st[r]);
 }
 
 // The four steps of one packed tile (stage registers st) of the segment [sb, se) of sorted positions,
@@ -99,16 +83,18 @@ __device__ __forceinline__ void stream_delta_issue(const Cursor &c, bool valid, 
 // of the window (the fragments in registers are not masked) into a copy of the accumulators; lanes
 // whose request column lies in the segment then keep the copy, the others keep what they had: one
 // select per accumulator register and task instead of a masked read of x per step.
-template <int BITS, int GROUP, int R, int J, int J0, int JW>
-__device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BITS, GROUP>::SD], int sb, int se,
+template <int BITS, int GROUP, bool QO, int R, int J, int J0, int JW>
+__device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BITS, GROUP, QO>::SD], int sb, int se,
                                                   const h16 (&bf)[4][WIN], const Geo &g, f4 (&acc)[R][J])
 {
-    typedef Fmt<BITS, GROUP> F;
+    typedef Fmt<BITS, GROUP, QO> F;
     f4 tmp[R][JW];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int j = 0; j < JW; ++j) tmp[r][j] = acc[r][J0 + j];
+#pragma unroll
+    for (int h = 0; h < F::NH; ++h)
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         h8 av[R];
@@ -118,9 +104,7 @@ __device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BI
             const h2 sz2 = as_h2(st[r][F::SC0 + s * F::GPT / 4]);
             const h2 s2 = (h2){sz2.x, sz2.x};
             const h2 z2 = (h2){sz2.y, sz2.y};
-            uint32_t w;
-            if (BITS == 4) { w = st[r][s]; idxw[r] = st[r][4 + (s >> 1)]; }
-            else { w = st[r][s >> 1] >> (8 * (s & 1)); idxw[r] = st[r][2 + (s >> 1)]; }
+            const uint32_t w = step_codes<BITS, QO>(st[r], s, h, idxw[r]);
             av[r] = dequant_step<BITS>(w, s2, z2);
         }
 #pragma unroll
@@ -152,11 +136,11 @@ __device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BI
 constexpr int DZ_RCAP_SMALL = 8;
 constexpr int DZ_RCAP_LARGE = 4;
 constexpr int DSTG = 3;
-template <int BITS, int GROUP, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
+template <int BITS, int GROUP, bool QO, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int round_tiles)
 {
-    typedef Fmt<BITS, GROUP> F;
+    typedef Fmt<BITS, GROUP, QO> F;
     constexpr int SD = F::SD;
     constexpr int THREADS = WAVES * 64;
     constexpr int ZROW = 16 * J;            // an all-zero LDS row for column slots without a request
@@ -299,7 +283,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
 #define DZ_ISSUE(buf)                                                                                              \
     do {                                                                                                           \
         const bool live = ti < nd0 || (ti >= nd0p && ti < nd);                                                     \
-        stream_delta_issue<BITS, GROUP, R>(ci, live, g, rtc, lo, tab, off_idx, off_scale, blob_bytes, buf);        \
+        stream_delta_issue<BITS, GROUP, QO, R>(ci, live, g, rtc, lo, tab, off_idx, off_scale, blob_bytes, buf);        \
         ++ti;                                                                                                      \
         if (NW > 1 && ti == nd0p) { ci.kt = kr0; ci.seg = wlo1; }                                                  \
         else if (ti < nd0) advance_seg(ci, wlo0, whi0);                                                            \
@@ -314,7 +298,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             if (cc.seg == slo) load_window_frags<J, J0, JW>(xs, brow, g, (cc.kt - kr0) * 256, bf);  /* new k tile */ \
             const int sb = __builtin_amdgcn_readlane(tab.sb, cc.seg);                                              \
             const int se = __builtin_amdgcn_readlane(tab.se, cc.seg);                                              \
-            stream_delta_task<BITS, GROUP, R, J, J0, JW>(cur, sb, se, bf, g, acc);                                 \
+            stream_delta_task<BITS, GROUP, QO, R, J, J0, JW>(cur, sb, se, bf, g, acc);                                 \
             advance_seg(cc, slo, shi);                                                                             \
         }                                                                                                          \
         ++tc;                                                                                                      \
@@ -575,11 +559,11 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
   }   // segments
 }
 
-template <int BITS, int GROUP, int WAVES, int R, int J, bool HB, bool HD>
+template <int BITS, int GROUP, bool QO, int WAVES, int R, int J, bool HB, bool HD>
 hipError_t launch_one(const DzStreamArgs &a, const DzGroup &gp, const DzGroupPtrs &dp, int NRB, int round_tiles, int grid,
                       size_t lds, hipStream_t st)
 {
-    auto k = stream_kernel<BITS, GROUP, WAVES, R, J, HB, HD>;
+    auto k = stream_kernel<BITS, GROUP, QO, WAVES, R, J, HB, HD>;
     static unsigned long long lds_allowed = 0;      // per instantiation
     const hipError_t e = dz_allow_lds((const void *)k, 160 * 1024 - 8192, lds_allowed);
     if (e != hipSuccess) return e;
@@ -587,36 +571,40 @@ hipError_t launch_one(const DzStreamArgs &a, const DzGroup &gp, const DzGroupPtr
     return hipGetLastError();
 }
 
-template <int BITS, int GROUP, int WAVES, int R, bool HB, bool HD>
+template <int BITS, int GROUP, bool QO, int WAVES, int R, bool HB, bool HD>
 hipError_t launch_j(int J, const DzStreamArgs &a, const DzGroup &gp, const DzGroupPtrs &dp, int NRB, int rt, int grid,
                     size_t lds, hipStream_t st)
 {
     switch (J) {
-    case 1: return launch_one<BITS, GROUP, WAVES, R, 1, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
-    case 2: return launch_one<BITS, GROUP, WAVES, R, 2, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
-    case 3: return launch_one<BITS, GROUP, WAVES, R, 3, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
-    default: return launch_one<BITS, GROUP, WAVES, R, 4, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
+    case 1: return launch_one<BITS, GROUP, QO, WAVES, R, 1, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
+    case 2: return launch_one<BITS, GROUP, QO, WAVES, R, 2, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
+    case 3: return launch_one<BITS, GROUP, QO, WAVES, R, 3, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
+    default: return launch_one<BITS, GROUP, QO, WAVES, R, 4, HB, HD>(a, gp, dp, NRB, rt, grid, lds, st);
     }
 }
 
-template <int WAVES, int R, bool HB, bool HD>
+template <bool QO, int WAVES, int R, bool HB, bool HD>
 hipError_t launch_fmt(int bits, int group, int J, const DzStreamArgs &a, const DzGroup &gp, const DzGroupPtrs &dp, int NRB,
                       int rt, int grid, size_t lds, hipStream_t st)
 {
-    if (!HD) return launch_j<4, 128, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
-    if (bits == 4 && group == 128) return launch_j<4, 128, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
-    if (bits == 4) return launch_j<4, 64, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
-    if (group == 128) return launch_j<2, 128, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
-    return launch_j<2, 64, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
+    if (!HD) return launch_j<4, 128, false, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
+    if (bits == 4 && group == 128) return launch_j<4, 128, QO, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
+    if (bits == 4) return launch_j<4, 64, QO, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
+    if (group == 128) return launch_j<2, 128, QO, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
+    return launch_j<2, 64, QO, WAVES, R, HB, HD>(J, a, gp, dp, NRB, rt, grid, lds, st);
 }
 
 template <int WAVES, int R>
 hipError_t launch_kind(const DzStreamArgs &a, int J, const DzGroup &gp, const DzGroupPtrs &dp, int NRB, int rt, int grid,
                        size_t lds, hipStream_t st)
 {
-    if (a.has_base && a.has_delta) return launch_fmt<WAVES, R, true, true>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
-    if (a.has_base) return launch_fmt<WAVES, R, true, false>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
-    return launch_fmt<WAVES, R, false, true>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
+    if (a.has_delta && a.quant_only) {
+        if (a.has_base) return launch_fmt<true, WAVES, R, true, true>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
+        return launch_fmt<true, WAVES, R, false, true>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
+    }
+    if (a.has_base && a.has_delta) return launch_fmt<false, WAVES, R, true, true>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
+    if (a.has_base) return launch_fmt<false, WAVES, R, true, false>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
+    return launch_fmt<false, WAVES, R, false, true>(a.bits, a.group, J, a, gp, dp, NRB, rt, grid, lds, st);
 }
 
 }  // namespace
@@ -632,13 +620,13 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group
     const int J = (a.T >= 64) ? 4 : (a.T + 15) / 16;
     // workgroup shape: 8 waves x 1 row tile (the B fragments of a k tile fill 32 J registers of every
     // wave during the delta phase, which leaves room for one row tile's accumulators and stage buffers)
-    int WAVES = ctx->wg_waves, R = ctx->wg_rtiles;
-    if (WAVES <= 0 || R <= 0) { WAVES = 8; R = 1; }
+    constexpr int WAVES = 8, R = 1;
     // row blocks of the projections, one projection after the other; a row block never spans two
     int NRB = 0, n_total = 0;
     for (int p = 0; p < gp.P; ++p) {
         if ((unsigned long long)gp.N[p] * a.K * 2ull >= (1ull << 32)) return DZ_ERR_SHAPE;     // 32-bit byte offsets
-        const DzLayout L = dz_make_layout(gp.N[p], a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
+        const DzLayout L = (a.has_delta && a.quant_only) ? dz_make_qlayout(gp.N[p], a.K, a.bits, a.group)
+                                                         : dz_make_layout(gp.N[p], a.K, a.has_delta ? a.bits : 4, a.has_delta ? a.group : 128);
         gp.off_idx[p] = (uint32_t)L.off_idx; gp.off_scale[p] = (uint32_t)L.off_scale; gp.blob_total[p] = (uint32_t)L.total;
         gp.rb_start[p] = NRB;
         gp.n_off[p] = n_total;
@@ -687,8 +675,6 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group
     const long long grid = (long long)nchunks * G;
     if (grid > 0x7fffffffLL) return DZ_ERR_SHAPE;
     hipError_t e;
-    if (WAVES == 8 && R == 1) e = launch_kind<8, 1>(a, J, gp, dp, NRB, round_tiles, (int)grid, lds, st);
-    else if (WAVES == 8 && R == 2) e = launch_kind<8, 2>(a, J, gp, dp, NRB, round_tiles, (int)grid, lds, st);
-    else e = launch_kind<4, 2>(a, J, gp, dp, NRB, round_tiles, (int)grid, lds, st);
+    e = launch_kind<WAVES, R>(a, J, gp, dp, NRB, round_tiles, (int)grid, lds, st);
     return dz_set_hip_error(ctx, e);
 }

@@ -186,7 +186,6 @@ def test_options_are_validated(dz):
     with dz.Context(0) as c:
         assert c.set_option(dz.DZ_OPT_SPLIT_K, 3) == dz.DZ_OK
         assert dz.dz_set_option(c.h, dz.DZ_OPT_WIDE_TILE, 3, check=False) == dz.DZ_ERR_ARG
-        assert dz.dz_set_option(c.h, dz.DZ_OPT_WG_SHAPE, 44, check=False) == dz.DZ_ERR_ARG
         assert dz.dz_set_option(c.h, 99, 1, check=False) == dz.DZ_ERR_ARG
         assert dz.dz_set_option(c.h, dz.DZ_OPT_SPLIT_K, -1, check=False) == dz.DZ_ERR_ARG
 
