@@ -241,6 +241,8 @@ def run_workload(args, name, steps, warmup, with_cpu, primary):
         # sampled output features of every projection of layer 0, as the timed step left them, against the oracle
         import numpy as np
         import oracle
+        step()                                  # the timed configuration once more: the comparison run above wrote `out` last
+        torch.cuda.synchronize()
         worst = 0.0
         for j, (pname, N, K, p) in enumerate(check_layer0):
             out = layers[0][j][5]

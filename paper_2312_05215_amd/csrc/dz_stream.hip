@@ -130,12 +130,15 @@ __device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BI
     }
 }
 
-// Tuned constants: k tiles of x an LDS round may hold (8 for one or two column blocks, 4 for three
-// or four: 135 KB either way, one workgroup per CU), and packed-tile stage buffers of the delta
-// phase (3: two tiles in flight while one computes).
-constexpr int DZ_RCAP_SMALL = 8;
-constexpr int DZ_RCAP_LARGE = 4;
+// An LDS round holds the x rows of RT2 k tiles (8 for one column block, 4 for two, 2 for three or four:
+// 66 KB either way), twice: while a round is multiplied, the x slice of the next one lands in the other
+// buffer, written there by buffer loads with an LDS destination (no staging registers; one load
+// instruction moves the 1 KB that two k tiles of one request row occupy).  DSTG: packed-tile stage
+// buffers of the delta phase (3: two tiles in flight while one computes).
+template <int J> struct RoundOf { static constexpr int TILES = (J == 1) ? 8 : (J == 2) ? 4 : 2; };
 constexpr int DSTG = 3;
+typedef __attribute__((address_space(3))) void lds_void;
+
 template <int BITS, int GROUP, bool QO, int WAVES, int R, int J, bool HAS_BASE, bool HAS_DELTA>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int round_tiles)
@@ -143,11 +146,14 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     typedef Fmt<BITS, GROUP, QO> F;
     constexpr int SD = F::SD;
     constexpr int THREADS = WAVES * 64;
+    constexpr int RT2 = RoundOf<J>::TILES;  // k tiles of x per LDS buffer
+    constexpr int LDW = RT2 * 256 + LDS_PAD;
     constexpr int ZROW = 16 * J;            // an all-zero LDS row for column slots without a request
-    // steps by which the W loads of the base phase run ahead: three with one row tile per wave, one
-    // with two (measured: 6 % faster on the 64-row shapes than three, 1 % slower on the 32-row ones)
-    constexpr int BDIST = (R == 1) ? 3 : 1;
-    extern __shared__ __attribute__((aligned(16))) _Float16 xs[];     // [16J + 1][LDW]
+    constexpr int BUFH = (16 * J + 1) * LDW;        // halfs per x buffer: the request rows, then the zero row
+    constexpr int XNI = 16 * J * (RT2 / 2) / WAVES; // LDS-destination loads per wave and round
+    static_assert((16 * J * (RT2 / 2)) % WAVES == 0 && R == 1, "round geometry");
+    constexpr int BDIST = 3;                // steps by which the W loads of the base phase run ahead
+    extern __shared__ __attribute__((aligned(16))) _Float16 xs[];     // 2 x [16J + 1][LDW]
     __shared__ int s_tok[64];               // request row of each sorted position (-1: none)
     __shared__ int s_key[64];               // delta of each sorted position
     __shared__ int s_raw[64];
@@ -163,7 +169,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     Geo g;
     g.lane = tid & 63; g.row = g.lane & 15; g.q = g.lane >> 4;
     g.KT = a.K >> 8;
-    g.LDW = round_tiles * 256 + LDS_PAD;
+    g.LDW = LDW;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     LaneOffs lo;
     lo.w = (uint32_t)g.row * (uint32_t)a.K * 2u + (uint32_t)g.q * 16u;
@@ -207,9 +213,14 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             }
             s_tok[tid] = tok;
             s_key[tid] = key;
-            s_boff[tid] = tid * g.LDW;
+            s_boff[tid] = tid * LDW;
         }
         lds_barrier();
+    }
+    // the zero rows of both buffers (no load ever writes them)
+    if (tid < LDW / 8) {
+        *(uint4 *)(xs + ZROW * LDW + tid * 8) = (uint4){0u, 0u, 0u, 0u};
+        *(uint4 *)(xs + BUFH + ZROW * LDW + tid * 8) = (uint4){0u, 0u, 0u, 0u};
     }
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.x, (uint32_t)a.T * (uint32_t)a.K * 2u);
@@ -217,6 +228,27 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     const int Tp = ((a.T + 63) >> 6) << 6;
     const uint32_t slice_bytes = (uint32_t)Tp * (uint32_t)a.N * 4u;
     const __amdgpu_buffer_rsrc_t prs = make_rsrc(a.partial, slice_bytes * (uint32_t)a.max_slots);
+    // ---- x[:, RT2 k tiles from kr on] -> LDS buffer bufi.  Unit u of the workgroup is request row
+    // u / (RT2 / 2), bytes 1024 * (u % (RT2 / 2)) .. + 1023 of that row's slice: one load instruction, lane l
+    // moving 16 bytes to LDS byte 16 l of the unit.  A row without a request, and the columns past the
+    // end of a row, get an offset beyond the resource: the hardware touches no memory for them (what
+    // lands in LDS there is never read: such columns belong to no k tile, such rows to no column slot).
+#define DZ_XDMA(bufi, kr)                                                                                          \
+    do {                                                                                                           \
+        _Pragma("unroll") for (int i = 0; i < XNI; ++i) {                                                         \
+            const int u = wave * XNI + i;                                                                          \
+            const int row = u / (RT2 / 2), piece = u % (RT2 / 2);                                                  \
+            const int tok = sort_here ? (row < cnt ? row : -1) : s_tok[row];                                       \
+            const int kcol = ((kr) + 2 * piece) * 256 + g.lane * 8;                                                \
+            const uint32_t vo = (tok >= 0 && kcol < a.K) ? (uint32_t)tok * (uint32_t)a.K * 2u + (uint32_t)g.lane * 16u \
+                                                         : 0xFFFFFFF0u;                                            \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void *)(xs + (bufi) * BUFH + row * LDW + piece * 512), 16, vo, \
+                                                     (uint32_t)((kr) + 2 * piece) * 512u, 0, 0);                   \
+        }                                                                                                          \
+    } while (0)
+    const int rtiles = (round_tiles > 0 && round_tiles < RT2) ? round_tiles : RT2;      // k tiles a round multiplies
+    int xbuf = 0;                                // the buffer that holds the current round's x
+    if (p_begin < p_end) DZ_XDMA(0, p_begin - (p_begin / g.KT) * g.KT);
     bool tables_ready = !sort_here;
     bool first_round = true;
     int nseg = 0;
@@ -258,10 +290,23 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int j = 0; j < J; ++j) acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
-    for (int kr0 = kt0; kr0 < kt1; kr0 += round_tiles) {
-        const int kr1 = min(kt1, kr0 + round_tiles);
+    // W ring of the base phase: named buffers (so each stays in registers), rotated by hand.  Inside a
+    // segment the pipeline runs on across the rounds: when a round ends, the first three steps of the
+    // next one are already in flight.
+    u32x4 bw0[R][2], bw1[R][2], bw2[R][2], bw3[R][2];
+    bool w_ahead = false;
+    for (int kr0 = kt0; kr0 < kt1; kr0 += rtiles) {
+        const int kr1 = min(kt1, kr0 + rtiles);
         const int ntr = kr1 - kr0;
         const int nsteps = 4 * ntr;              // base steps of this round
+        const int seg_last = 4 * (kt1 - kr0) - 1;    // last base step of the segment, counted from this round's start
+        const _Float16 *xc = xs + xbuf * BUFH;   // this round's x
+        // ---- the next round's x starts its way into the other buffer (everybody left that buffer at
+        // the barrier that ended the previous round)
+        {
+            const int nk = kr1 < kt1 ? kr1 : p - (p / g.KT) * g.KT;
+            if (kr1 < kt1 || p < p_end) DZ_XDMA(xbuf ^ 1, nk);
+        }
         // Delta tasks of this round, in issue order: window 0's (k tile by k tile, all of its segments per
         // k tile), padded to a multiple of the stage-buffer count so that window 1's start at rotation
         // phase 0, then window 1's.  Set after the sort in round one.
@@ -269,11 +314,9 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         Cursor ci, cc;
         ci.kt = kr0; ci.seg = wlo0;
         cc = ci;
-        // named stage buffers (so each stays in registers), rotated by hand.  Issue cursors stop at
-        // the last task / step and re-issue it (a few redundant cache hits at the end of a round)
-        // so that issuing needs no branch.
+        // named stage buffers, rotated by hand.  Issue cursors stop at the last task / step and
+        // re-issue it (a few redundant cache hits at the end of a segment) so that issuing needs no branch.
         uint32_t st0[R][SD], st1[R][SD], st2[R][SD];
-        u32x4 bw0[R][2], bw1[R][2], bw2[R][2], bw3[R][2];
         uint32_t wbase[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) wbase[r] = ((uint32_t)rtc[r] * 16u * (uint32_t)a.K + (uint32_t)kr0 * 256u) * 2u;
@@ -283,7 +326,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
 #define DZ_ISSUE(buf)                                                                                              \
     do {                                                                                                           \
         const bool live = ti < nd0 || (ti >= nd0p && ti < nd);                                                     \
-        stream_delta_issue<BITS, GROUP, QO, R>(ci, live, g, rtc, lo, tab, off_idx, off_scale, blob_bytes, buf);        \
+        stream_delta_issue<BITS, GROUP, QO, R>(ci, live, g, rtc, lo, tab, off_idx, off_scale, blob_bytes, buf);    \
         ++ti;                                                                                                      \
         if (NW > 1 && ti == nd0p) { ci.kt = kr0; ci.seg = wlo1; }                                                  \
         else if (ti < nd0) advance_seg(ci, wlo0, whi0);                                                            \
@@ -295,67 +338,28 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         const int slo = (W) ? wlo1 : wlo0, shi = (W) ? whi1 : whi0;                                                \
         DZ_ISSUE(nxt);                                                                                             \
         if (tc < ((W) ? nd : nd0)) {                                                                               \
-            if (cc.seg == slo) load_window_frags<J, J0, JW>(xs, brow, g, (cc.kt - kr0) * 256, bf);  /* new k tile */ \
+            if (cc.seg == slo) load_window_frags<J, J0, JW>(xc, brow, g, (cc.kt - kr0) * 256, bf);  /* new k tile */ \
             const int sb = __builtin_amdgcn_readlane(tab.sb, cc.seg);                                              \
             const int se = __builtin_amdgcn_readlane(tab.se, cc.seg);                                              \
-            stream_delta_task<BITS, GROUP, QO, R, J, J0, JW>(cur, sb, se, bf, g, acc);                                 \
+            stream_delta_task<BITS, GROUP, QO, R, J, J0, JW>(cur, sb, se, bf, g, acc);                             \
             advance_seg(cc, slo, shi);                                                                             \
         }                                                                                                          \
         ++tc;                                                                                                      \
     } while (0)
 #define DZ_BSTEP(s, cur, nxt)                                                                                      \
     do {                                                                                                           \
-        base_issue<R>(rw, wbase, lo.w, min((s) + BDIST, nsteps - 1), nxt);                                             \
-        base_compute<R, J>(cur, xs, g, brow, (s) * 64, acc);                                                       \
+        base_issue<R>(rw, wbase, lo.w, min((s) + BDIST, seg_last), nxt);                                           \
+        base_compute<R, J>(cur, xc, g, brow, (s) * 64, acc);                                                       \
     } while (0)
-        if (!first_round) lds_barrier();       // previous LDS readers are done
-        // ---- x[:, k-slice of this round] -> LDS (rows past cnt zero).  Order of issue: x first
-        // (loads return in order and x is needed first), then the first weight loads, which then
-        // fly while the batch is being sorted and x is written to LDS.
-        const int cpr = ntr * 32;                // 16-byte pieces per row
-        const int npieces = 16 * J * cpr;
-        const uint32_t rcp = (65536u + (uint32_t)ntr - 1u) / (uint32_t)ntr;
-        // two batches of loads per thread cover the largest round: the first is written to LDS
-        // right away, the second stays in registers while the weight prefetch is issued behind it
-        // (one batch for the whole slice would not fit the registers next to that prefetch)
-        constexpr int XB = (16 * J * ((J <= 2) ? DZ_RCAP_SMALL : DZ_RCAP_LARGE) * 32 + 2 * THREADS - 1) / (2 * THREADS);
-        u32x4 xv[XB];
-        int xdst[XB];
-#define DZ_XLOAD(i0)                                                                                               \
-    do {                                                                                                           \
-        _Pragma("unroll") for (int u = 0; u < XB; ++u) {                                                          \
-            const int i = (i0) + u * THREADS;                                                                      \
-            const int rr = (int)((((uint32_t)i >> 5) * rcp) >> 16);                                                \
-            const int cc2 = i - rr * cpr;                                                                          \
-            int tok = -1;                                                                                          \
-            if (i < npieces) tok = sort_here ? (rr < cnt ? rr : -1) : s_tok[rr];                                   \
-            xdst[u] = (i < npieces) ? rr * g.LDW + cc2 * 8 : -1;                                                   \
-            /* a row that does not exist gets an offset beyond the resource and reads zeros */                     \
-            const uint32_t xo = tok >= 0 ? (uint32_t)tok * (uint32_t)a.K * 2u + (uint32_t)kr0 * 512u + (uint32_t)cc2 * 16u \
-                                         : 0xFFFFFFF0u;                                                            \
-            xv[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, xo, 0, 0);                                           \
-        }                                                                                                          \
-    } while (0)
-#define DZ_XSTORE()                                                                                                \
-    do {                                                                                                           \
-        _Pragma("unroll") for (int u = 0; u < XB; ++u)                                                            \
-            if (xdst[u] >= 0) *(u32x4 *)(xs + xdst[u]) = xv[u];                                                    \
-    } while (0)
-        int xb0 = 0;
-        for (; xb0 + THREADS * XB < npieces; xb0 += THREADS * XB) {
-            DZ_XLOAD(xb0 + tid);
-            DZ_XSTORE();
-        }
-        DZ_XLOAD(xb0 + tid);
         if constexpr (HAS_BASE) {
-            base_issue<R>(rw, wbase, lo.w, 0, bw0);
-            if constexpr (BDIST == 3) {
-                base_issue<R>(rw, wbase, lo.w, min(1, nsteps - 1), bw1);
-                base_issue<R>(rw, wbase, lo.w, min(2, nsteps - 1), bw2);
+            if (!w_ahead) {                      // first round of a segment: the weight loads start here and
+                base_issue<R>(rw, wbase, lo.w, 0, bw0);             // fly while the batch is being sorted
+                base_issue<R>(rw, wbase, lo.w, min(1, seg_last), bw1);
+                base_issue<R>(rw, wbase, lo.w, min(2, seg_last), bw2);
             }
         }
         if (!tables_ready) {
-            // ---- rank the batch (all threads; four short barriers)
+            // ---- rank the batch (all threads; three short barriers)
             if (tid < 64) {
                 int key = INT_MAX;
                 if (tid < cnt) {
@@ -385,7 +389,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
                 const int r = s_rank[tid];
                 s_tok[r] = tid < cnt ? tid : -1;
                 s_key[r] = s_raw[tid];
-                s_boff[r] = (tid < cnt ? tid : ZROW) * g.LDW;
+                s_boff[r] = (tid < cnt ? tid : ZROW) * LDW;
             }
             lds_barrier();
         }
@@ -408,7 +412,9 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
                     s_seg_begin[ns] = __builtin_popcountll(vm);     // rows that name a delta are a prefix
                 }
             }
-            if (tid < g.LDW / 8) *(uint4 *)(xs + ZROW * g.LDW + tid * 8) = (uint4){0u, 0u, 0u, 0u};
+            // this wave's pieces of the first x slice have landed (and so have its first weight loads,
+            // which the base phase needs at once anyway); after the barrier everybody's have
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             lds_barrier();
             tables_ready = true;
             nseg = HAS_DELTA ? s_nseg : 0;
@@ -430,6 +436,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             ci.seg = cc.seg = wlo0;
 #pragma unroll
             for (int j = 0; j < J; ++j) brow[j] = s_boff[16 * j + g.row];
+            first_round = false;
         }
         SegTable tab = {0u, 0u, 0, 0};
         if constexpr (HAS_DELTA) {
@@ -441,23 +448,14 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             DZ_ISSUE(st0);
             DZ_ISSUE(st1);
         }
-        DZ_XSTORE();
-        lds_barrier();
-        first_round = false;
         if constexpr (HAS_BASE) {
             for (int s = 0; s < nsteps; s += 4) {
-                if constexpr (BDIST == 3) {
-                    DZ_BSTEP(s, bw0, bw3);
-                    DZ_BSTEP(s + 1, bw1, bw0);
-                    DZ_BSTEP(s + 2, bw2, bw1);
-                    DZ_BSTEP(s + 3, bw3, bw2);
-                } else {
-                    DZ_BSTEP(s, bw0, bw1);
-                    DZ_BSTEP(s + 1, bw1, bw0);
-                    DZ_BSTEP(s + 2, bw0, bw1);
-                    DZ_BSTEP(s + 3, bw1, bw0);
-                }
+                DZ_BSTEP(s, bw0, bw3);
+                DZ_BSTEP(s + 1, bw1, bw0);
+                DZ_BSTEP(s + 2, bw2, bw1);
+                DZ_BSTEP(s + 3, bw3, bw2);
             }
+            w_ahead = true;                      // bw0 .. bw2 now hold (or await) steps 0 .. 2 of the next round
         }
         if constexpr (HAS_DELTA) {
             static_assert(DSTG == 3, "the rotation below is written for three stage buffers");
@@ -479,9 +477,15 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
 #undef DZ_ISSUE
 #undef DZ_STEP
 #undef DZ_BSTEP
-#undef DZ_XLOAD
-#undef DZ_XSTORE
+        // ---- end of the round: everybody is done with this round's x, and the next round's is complete.
+        // A wave's pieces of it were requested before every weight load of this round; loads return
+        // in order, so a wave that has consumed one of those has its pieces in LDS.  A launch without
+        // a base product may have consumed nothing: it waits for whatever it still has in flight.
+        if constexpr (!HAS_BASE) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        lds_barrier();
+        xbuf ^= 1;
     }
+#undef DZ_XDMA
 
     // ---- results of this segment: lane 16q + c holds rows 4q..4q+3 of the row tile for request
     // column c.  Which workgroups contribute to row block rb follows from the range formula:
@@ -656,12 +660,10 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group
     const size_t Tp = (size_t)nchunks * 64;
     if ((size_t)max_slots * Tp * a.N * 4 >= ((size_t)1 << 32)) return DZ_ERR_SHAPE;    // 32-bit byte offsets
     if ((unsigned long long)a.T * a.K * 2ull >= 0xFFFFFFF0ull) return DZ_ERR_SHAPE;
-    // one batch of x loads per thread must cover a round (see XB in the kernel)
-    const int round_cap = (J <= 2 ? DZ_RCAP_SMALL : DZ_RCAP_LARGE);
-    int round_tiles = (ctx->round_tiles > 0 && ctx->round_tiles < round_cap) ? ctx->round_tiles : round_cap;
-    const int max_slice = (int)((P + G - 1) / G) < KT ? (int)((P + G - 1) / G) : KT;
-    if (round_tiles > max_slice) round_tiles = max_slice;
-    const size_t lds = (size_t)(16 * J + 1) * (round_tiles * 256 + LDS_PAD) * sizeof(_Float16);
+    // k tiles per round: what one of the two x buffers in LDS holds (RoundOf in the kernel), or fewer on request
+    const int round_cap = (J == 1) ? 8 : (J == 2) ? 4 : 2;
+    const int round_tiles = (ctx->round_tiles > 0 && ctx->round_tiles < round_cap) ? ctx->round_tiles : round_cap;
+    const size_t lds = (size_t)2 * (16 * J + 1) * (round_cap * 256 + LDS_PAD) * sizeof(_Float16);
     a.S = (int)G;
     a.max_slots = max_slots;
     if (max_slots > 1) {

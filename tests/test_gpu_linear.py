@@ -182,6 +182,24 @@ def test_base_gemm_of_a_large_batch_over_several_tiles(dz, opts):
         assert_close(o, ref, f"base gemm {opts}")
 
 
+@pytest.mark.parametrize("tiles", [1, 2, 3])
+@pytest.mark.parametrize("case", [("b4g128_t32", 32, 96, 2048, 8, 4, 128, "uniform"), ("b2g128_t64z", 64, 160, 2304, 32, 2, 128, "zipf"),
+                                  ("b4g64_t9", 9, 272, 2816, 3, 4, 64, "uniform"), ("b2g64_t40", 40, 48, 1792, 5, 2, 64, "uniform")],
+                         ids=lambda c: c[0])
+def test_short_rounds(dz, case, tiles):
+    """DZ_OPT_ROUND_TILES below what the LDS buffers hold: many rounds per workgroup, so the two x buffers
+    swap several times inside a row block, with and without split k."""
+    name, T, N, K, D, bits, G, ids = case
+    print(f"case {name} round tiles {tiles}", flush=True)
+    for splits in (0, 1, 2):
+        with dz.Context(0) as c:
+            c.set_option(dz.DZ_OPT_ROUND_TILES, tiles)
+            if splits:
+                c.set_option(dz.DZ_OPT_SPLIT_K, splits)
+            cs = Case(dz, c.h, 5, T, N, K, D, bits, G, ids)
+            _run_all(dz, c, cs, f"{name} round tiles {tiles} splits {splits}")
+
+
 def test_options_are_validated(dz):
     with dz.Context(0) as c:
         assert c.set_option(dz.DZ_OPT_SPLIT_K, 3) == dz.DZ_OK
