@@ -69,10 +69,10 @@ def parse():
     return ap.parse_args()
 
 
-def profile_traffic(workload: str, launches_per_layer: int):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if one exists for the
-    same launch grouping.  A stored figure of an earlier run of the same command, not measured in this run."""
-    path = os.path.join(ROOT, "profiles", f"stream_kernel_{workload}_pmc.txt")
+def profile_traffic(kernel: str, workload: str, launches_per_layer: int):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and workload, if one exists
+    for the same launch grouping.  A stored figure of an earlier run of the same command, not measured in this run."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
     try:
         prof = {}
         for ln in open(path):
@@ -208,14 +208,16 @@ def run_workload(args, name, steps, warmup, with_cpu, primary):
     ms_model = ms_per_step * cfg.layers / n_layers
     tokens_per_s = cfg.T / (ms_model * 1e-3)
 
-    launches_per_layer = len(groups) if grouped else len(projs)
+    # kernel launches per layer: one per call for small batches; large batches run one tiled kernel per projection
+    launches_per_layer = len(groups) if (grouped and cfg.T <= 64) else len(projs)
     launches_per_step = n_layers * launches_per_layer
     act = 0 if path == "base" else n_active
     bytes_per_step = n_layers * sum(S.algorithmic_bytes(N, K, cfg.T, cfg.bits, cfg.group, act) - (2 * N * K if path == "sbmm" else 0)
                                     for _, N, K in projs)
     avg_launch_us = ms_per_step * 1e3 / launches_per_step
     achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
-    traffic, traffic_src = profile_traffic(cfg.name, launches_per_layer) if path == "linear" else (None, None)
+    traffic, traffic_src = (profile_traffic("stream_kernel" if cfg.T <= 64 else "prefill_kernel", cfg.name, launches_per_layer)
+                            if path == "linear" else (None, None))
     roofline = {"bound": "hbm", "kernel": "stream_kernel (fused base GEMM + SBMM)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "traffic_source": traffic_src,
@@ -233,7 +235,8 @@ def run_workload(args, name, steps, warmup, with_cpu, primary):
                  "sbmm": "prefill_kernel (SBMM)"}[path]
         roofline = {"bound": "mfma", "kernel": kname, "achieved": round(tf, 1),
                     "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4),
-                    "traffic": None, "flops_per_launch_avg": int(flops_per_step // launches_per_step),
+                    "traffic": traffic, "traffic_source": traffic_src,
+                    "flops_per_launch_avg": int(flops_per_step // launches_per_step),
                     "avg_launch_us": round(avg_launch_us, 2), "launches_per_step": launches_per_step}
 
     checked = None

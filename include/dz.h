@@ -33,9 +33,9 @@
  *
  * Ownership and synchronisation: the caller owns every buffer it passes.  The library owns only
  * the workspace inside dz_ctx (segment tables, split-K partial sums, an error flag), which may grow
- * on a call that needs more than any earlier call (that growth synchronises the stream once; the
- * buffer it replaces stays allocated until dz_destroy, so a HIP graph recorded before the growth can
- * still be replayed).
+ * on a call that needs more than any earlier call (that growth allocates -- it does not wait for the
+ * stream; the buffer it replaces stays allocated until dz_destroy, so launches still in flight keep it
+ * and a HIP graph recorded before the growth can still be replayed).
  * A stream that is being captured into a HIP graph can be passed once an eager call with the same
  * shapes has sized the workspace: the calls then record only kernels.  A call that would have to
  * grow the workspace during a capture returns DZ_ERR_HIP and records nothing.

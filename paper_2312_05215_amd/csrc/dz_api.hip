@@ -43,17 +43,23 @@ int dz_set_hip_error(dz_ctx *ctx, hipError_t e)
     return DZ_ERR_HIP;
 }
 
-// The workspace can only grow between launches: growing synchronises the stream and allocates,
-// neither of which a stream that is being recorded into a graph allows.  Such a call fails here,
-// before it touches the stream, so the capture itself stays valid.
+__global__ void dz_clear_words_kernel(int32_t *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// The workspace grows by allocating, which a stream that is being recorded into a graph does not
+// allow.  Such a call fails here, before it touches the stream, so the capture itself stays valid.
+// Nothing waits for the stream: launches that are still running keep the buffer they were given
+// (a replaced buffer is retired, not freed).
 static int quiesce_for_growth(dz_ctx *ctx, hipStream_t st)
 {
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     hipError_t e = hipStreamIsCapturing(st, &cs);
     if (e != hipSuccess) return dz_set_hip_error(ctx, e);
     if (cs != hipStreamCaptureStatusNone) return dz_set_hip_error(ctx, hipErrorStreamCaptureUnsupported);
-    e = hipStreamSynchronize(st);                       // earlier launches may still read the old buffer
-    return dz_set_hip_error(ctx, e);
+    return DZ_OK;
 }
 
 // A buffer that a growth replaces is kept until dz_destroy: the kernel nodes of a HIP graph recorded
@@ -92,7 +98,9 @@ int dz_ensure_counters(dz_ctx *ctx, int n, hipStream_t st)
     int want = n * 2;
     hipError_t e = hipMalloc((void **)&ctx->counters, (size_t)want * 4);
     if (e != hipSuccess) return dz_set_hip_error(ctx, e);
-    e = hipMemset(ctx->counters, 0, (size_t)want * 4);
+    // cleared on the caller's stream, ahead of the launch that asked for them
+    hipLaunchKernelGGL(dz_clear_words_kernel, dim3((unsigned)((want + 255) / 256)), dim3(256), 0, st, ctx->counters, want);
+    e = hipGetLastError();
     if (e != hipSuccess) return dz_set_hip_error(ctx, e);
     ctx->counters_cap = want;
     return DZ_OK;
@@ -135,12 +143,6 @@ static int ensure_seg(dz_ctx *ctx, int T, hipStream_t st)
 // The entry point that allocates nothing keeps a sticky error word of its own per GPU; dz_check
 // reports it too when that translation unit is part of the library.
 extern "C" int32_t *dz_static_err_word(int device) __attribute__((weak));
-
-__global__ void dz_clear_words_kernel(int32_t *p, int n)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
-}
 
 extern "C" {
 
