@@ -125,6 +125,41 @@ def test_merged_weight(dz, N, K, bits, G, T):
         assert dz.dz_check(c.h) == dz.DZ_OK
 
 
+def test_two_of_four_delta_written_densely_serves_the_same(dz):
+    """Dense-expanded serving of a 2:4 delta: the same delta written into the quantisation-only format
+    (pruned columns carry the zero-point as their code) goes through dz_qsbmm at the dense rate and must
+    match both the oracle and, to rounding, dz_sbmm on the 2:4 blob."""
+    T, N, K, D, bits, G = 48, 128, 1024, 3, 4, 128
+    x = S.make_x(T, K, S.stream(44, "x"))
+    ids = _ids("uniform", T, D, 44)
+    tabs = [S.make_delta_tables(N, K, bits, G, S.stream(44, "delta", m)) for m in range(D)]
+    dense = [oracle.c.dequant(t.codes.numpy(), t.idx.numpy(), t.scale.numpy(), t.zero.numpy(), bits, G) for t in tabs]
+    want = oracle.c.linear(x.numpy(), None, dense, ids.numpy())
+    with dz.Context(0) as c:
+        sp, qp = [], []
+        for t in tabs:
+            d = t.to("cuda")
+            p = torch.empty(dz.dz_packed_bytes(N, K, bits, G), dtype=torch.uint8, device="cuda")
+            dz.dz_pack_delta(c.h, d.codes, d.idx, d.scale, d.zero, N, K, bits, G, p)
+            sp.append(p)
+            codes = np.repeat(t.zero.numpy().astype(np.uint8), G, axis=1)
+            cols = (np.arange(K // 2) // 2 * 4)[None, :] + t.idx.numpy().astype(np.int64)
+            np.put_along_axis(codes, cols, t.codes.numpy(), axis=1)
+            q = torch.empty(dz.dz_qpacked_bytes(N, K, bits, G), dtype=torch.uint8, device="cuda")
+            dz.dz_qpack_delta(c.h, torch.from_numpy(codes).cuda(), d.scale, d.zero, N, K, bits, G, q)
+            qp.append(q)
+        o_s = torch.empty(T, N, dtype=torch.float16, device="cuda")
+        o_q = torch.empty(T, N, dtype=torch.float16, device="cuda")
+        dz.dz_sbmm(c.h, x.cuda(), sp, ids.cuda(), o_s, T, N, K, bits, G, 0)
+        dz.dz_qsbmm(c.h, x.cuda(), qp, ids.cuda(), o_q, T, N, K, bits, G, 0)
+        torch.cuda.synchronize()
+        assert_close(o_s, want, "2:4 blob")
+        assert_close(o_q, want, "the same delta, dense-expanded")
+        # identical dequantised values, identical k order inside a step: the two differ by summation order only
+        assert (o_s.float() - o_q.float()).abs().max().item() <= 2.0 ** -9 * float(np.abs(want).max())
+        assert dz.dz_check(c.h) == dz.DZ_OK
+
+
 def test_argument_errors(dz):
     with dz.Context(0) as c:
         z = torch.zeros(16 * 256, dtype=torch.uint8, device="cuda")
