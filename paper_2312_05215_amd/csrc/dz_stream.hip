@@ -191,6 +191,33 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     const int p0 = chunk * 64;
     const int cnt = min(64, a.T - p0);
 
+    // W ring of the base phase: named buffers (so each stays in registers), rotated by hand.  Inside a
+    // piece the pipeline runs on across the rounds: when a round ends, the first three steps of the
+    // next one are already in flight.  The very first weight loads of the workgroup go out here, before
+    // anything else is set up: they take longest to arrive (first touch of this launch's weights) and
+    // the rest of the start-up -- tables, the x slice, the ranking of the batch -- runs under them.
+    u32x4 bw0[R][2], bw1[R][2], bw2[R][2], bw3[R][2];
+    bool w_ahead = false;
+    if (HAS_BASE && p_begin < p_end) {
+        const int rb = p_begin / g.KT;
+        const int kt0 = p_begin - rb * g.KT;
+        const int steps = 4 * min(g.KT - kt0, p_end - p_begin);
+        int pj = 0;
+        while (pj + 1 < gp.P && rb >= gp.rb_start[pj + 1]) ++pj;
+        const int Np = gp.N[pj];
+        const __amdgpu_buffer_rsrc_t rw = make_rsrc(gp.W[pj], (uint32_t)Np * (uint32_t)a.K * 2u);
+        uint32_t wbase[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int rt = min((rb - gp.rb_start[pj]) * (WAVES * R) + wave * R + r, (Np >> 4) - 1);
+            wbase[r] = ((uint32_t)rt * 16u * (uint32_t)a.K + (uint32_t)kt0 * 256u) * 2u;
+        }
+        base_issue<R>(rw, wbase, lo.w, 0, bw0);
+        base_issue<R>(rw, wbase, lo.w, min(1, steps - 1), bw1);
+        base_issue<R>(rw, wbase, lo.w, min(2, steps - 1), bw2);
+        w_ahead = true;
+    }
+
     // Request order (paper Section 5.2: requests of one delta are grouped).  Batches of up to 64
     // rows are ranked by every workgroup itself from the raw index vector (rank = rows with a
     // smaller delta + earlier rows of the same delta) -- no extra launch and no dependent load;
@@ -198,10 +225,11 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     // Larger batches read the sorted order a segment pass left in the workspace and stage x rows
     // already sorted.
     const bool sort_here = HAS_DELTA && a.ids != nullptr;
-    if (HAS_DELTA) {                                               // before any long-latency load
-        for (int i = tid; i < max(gp.P * a.D, 1); i += THREADS)
-            s_dptr[i] = i < gp.P * a.D ? (unsigned long long)dp.p[i] : (unsigned long long)a.x;
-    }
+    // this thread's entry of the packed-delta pointer table: requested now, written to LDS behind the
+    // sort (a write here would have to wait for every load requested so far, the weights included)
+    static_assert(DZ_GROUP_PTRS <= THREADS, "one pointer per thread");
+    unsigned long long my_dptr = (unsigned long long)a.x;
+    if (HAS_DELTA && tid < gp.P * a.D) my_dptr = (unsigned long long)dp.p[tid];
     int my_id = -1;
     if (sort_here && tid < cnt) my_id = a.ids[tid];                 // earliest possible load
     if (!sort_here) {
@@ -290,11 +318,6 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int j = 0; j < J; ++j) acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
-    // W ring of the base phase: named buffers (so each stays in registers), rotated by hand.  Inside a
-    // segment the pipeline runs on across the rounds: when a round ends, the first three steps of the
-    // next one are already in flight.
-    u32x4 bw0[R][2], bw1[R][2], bw2[R][2], bw3[R][2];
-    bool w_ahead = false;
     for (int kr0 = kt0; kr0 < kt1; kr0 += rtiles) {
         const int kr1 = min(kt1, kr0 + rtiles);
         const int ntr = kr1 - kr0;
@@ -394,6 +417,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             lds_barrier();
         }
         if (first_round) {
+            if (HAS_DELTA && tid < max(gp.P * a.D, 1)) s_dptr[tid] = my_dptr;
             if (HAS_DELTA && tid < 64) {
                 const int key = s_key[tid];
                 const int prev = tid ? s_key[tid - 1] : -1;
@@ -485,7 +509,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         lds_barrier();
         xbuf ^= 1;
     }
-#undef DZ_XDMA
+    w_ahead = false;                             // the next piece starts its own weight loads
 
     // ---- results of this segment: lane 16q + c holds rows 4q..4q+3 of the row tile for request
     // column c.  Which workgroups contribute to row block rb follows from the range formula:
@@ -561,6 +585,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         }
     }
   }   // segments
+#undef DZ_XDMA
 }
 
 template <int BITS, int GROUP, bool QO, int WAVES, int R, int J, bool HB, bool HD>
