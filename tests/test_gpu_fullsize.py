@@ -186,3 +186,64 @@ def test_grouped_split_k_launch_is_reproducible(dz):
             for a, b in zip(first, outs):
                 assert torch.equal(a, b), f"repeat {rep} differs"
         assert dz.dz_check(c.h) == dz.DZ_OK
+
+
+@pytest.mark.parametrize("cfgname,N,K", [("7b_decode", 11008, 4096), ("70b_stack", 8192, 8192), ("13b_prefill", 5120, 5120)],
+                         ids=lambda v: str(v))
+def test_fullsize_quantisation_only(dz, cfgname, N, K):
+    """dz_qlinear at workload sizes (quantisation-only deltas: Section 4.1 step 3 without step 2), sampled
+    output features against the oracle; the deltas are quantised on the GPU by the seeded generator."""
+    print(f"case {cfgname} quant-only {N}x{K}", flush=True)
+    cfg = S.config(cfgname)
+    D = min(cfg.D, 4)
+    with dz.Context(0) as c:
+        W = S.make_base(N, K, S.stream(0, cfgname, "qfull", "W", device="cuda"))
+        x = S.make_x(cfg.T, K, S.stream(0, cfgname, "qfull", "x", device="cuda"))
+        tabs = [S.make_dense_tables(N, K, cfg.bits, cfg.group, S.stream(0, cfgname, "qfull", m, device="cuda")) for m in range(D)]
+        ids = cfg.make_ids(S.stream(0, cfg.name, "ids")) % D
+        ids = ids.to(torch.int32)
+        packed = []
+        for t in tabs:
+            p = torch.empty(dz.dz_qpacked_bytes(N, K, cfg.bits, cfg.group), dtype=torch.uint8, device="cuda")
+            dz.dz_qpack_delta(c.h, t.codes, t.scale, t.zero, N, K, cfg.bits, cfg.group, p)
+            packed.append(p)
+        out = torch.full((cfg.T, N), 7.0, dtype=torch.float16, device="cuda")
+        dz.dz_qlinear(c.h, x, W, packed, ids.cuda(), out, cfg.T, N, K, cfg.bits, cfg.group)
+        assert dz.dz_check(c.h) == dz.DZ_OK
+        rows = _sample_rows(N)
+        ridx = torch.as_tensor(rows, device="cuda")
+        dense = [oracle.quant.dequant_dense(t.codes[ridx].cpu().numpy(), t.scale[ridx].cpu().numpy(),
+                                            t.zero[ridx].cpu().numpy(), cfg.bits, cfg.group) for t in tabs]
+        ref = oracle.c.linear(x.cpu().numpy(), W[ridx].cpu().numpy(), dense, ids.numpy())
+        max_rel, mean_abs = assert_close(out[:, ridx], ref, f"{cfgname} quant-only {N}x{K}")
+        print(f"  max_rel={max_rel:.2e} mean_abs={mean_abs:.2e}", flush=True)
+
+
+def test_fullsize_adapters_and_compressor(dz):
+    """dz_lora_sbmm with 128 adapters of rank 64 on a 7B projection, and dz_compress_delta on a whole
+    4096 x 4096 delta (bit-exact against the oracle on sampled rows, which are independent of each other)."""
+    T, N, K, D, r = 64, 4096, 4096, 128, 64
+    with dz.Context(0) as c:
+        x = S.make_x(T, K, S.stream(0, "lora full", "x", device="cuda"))
+        A = [S.make_base(r, K, S.stream(0, "lora full", "A", m, device="cuda"), 0.05) for m in range(D)]
+        B = [S.make_base(N, r, S.stream(0, "lora full", "B", m, device="cuda"), 0.05) for m in range(D)]
+        ids = S.ids_uniform(T, D, S.stream(0, "lora full", "ids")).to(torch.int32)
+        out = torch.empty(T, N, dtype=torch.float16, device="cuda")
+        dz.dz_lora_sbmm(c.h, x, A, B, r, ids.cuda(), out, T, N, K, 0)
+        torch.cuda.synchronize()
+        used = sorted(set(int(v) for v in ids.tolist()))
+        remap = {m: i for i, m in enumerate(used)}
+        ref = oracle.lora.lora_sbmm(x.cpu().numpy(), [A[m].cpu().numpy() for m in used], [B[m].cpu().numpy() for m in used],
+                                    np.asarray([remap[int(v)] for v in ids.tolist()], np.int32))
+        assert_close(out, ref, "128 adapters of rank 64")
+        d = S._normal_f16((N, K), 0.002, S.stream(0, "compress full", device="cuda"))
+        codes = torch.empty(N, K // 2, dtype=torch.uint8, device="cuda"); idx = torch.empty_like(codes)
+        scale = torch.empty(N, K // 128, dtype=torch.float16, device="cuda"); zero = torch.empty_like(scale)
+        dz.dz_compress_delta(c.h, d, N, K, 4, 128, codes, idx, scale, zero)
+        torch.cuda.synchronize()
+        rows = torch.as_tensor(_sample_rows(N), device="cuda")
+        wc, wi, ws, wz = oracle.compress_.compress(d[rows].cpu().numpy(), 4, 128)
+        assert np.array_equal(codes[rows].cpu().numpy(), wc) and np.array_equal(idx[rows].cpu().numpy(), wi)
+        assert np.array_equal(scale[rows].cpu().numpy().view(np.uint16), ws.view(np.uint16))
+        assert np.array_equal(zero[rows].cpu().numpy().view(np.uint16), wz.view(np.uint16))
+        assert dz.dz_check(c.h) == dz.DZ_OK
