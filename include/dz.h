@@ -60,7 +60,7 @@ extern "C" {
 #define DZ_ERR_SHAPE  (-2)  /* N, K, group outside the accepted shapes listed above                  */
 #define DZ_ERR_BITS   (-3)  /* bits not 2 or 4                                                       */
 #define DZ_ERR_ALIGN  (-4)  /* a device pointer is not 16-byte aligned                               */
-#define DZ_ERR_HIP    (-5)  /* the HIP runtime reported a failure (text from dz_last_hip_error)      */
+#define DZ_ERR_HIP    (-5)  /* the HIP runtime reported a failure (its text: dz_strerror on this thread) */
 #define DZ_ERR_INDEX  (-6)  /* dz_check: some earlier call saw a request index outside [-1, D)       */
 #define DZ_ERR_LIMIT  (-7)  /* the call needs more workspace than the entry point or context may use */
 
@@ -70,7 +70,8 @@ extern "C" {
 
 typedef struct dz_ctx dz_ctx;
 
-/* Static text for a return code. */
+/* Text for a return code: static, except for DZ_ERR_HIP, where it carries the HIP runtime's own text of
+ * the calling thread's last failure (a thread-local buffer, valid until that thread's next failure). */
 const char *dz_strerror(int rc);
 /* Text of the last HIP failure seen through this context ("" if none).  Valid until the next call. */
 const char *dz_last_hip_error(const dz_ctx *ctx);

@@ -1,6 +1,7 @@
 // C ABI of libdz (include/dz.h): argument checks, the context's workspace, and dispatch to the
 // kernels.  No compute happens here.
 #include "dz_internal.h"
+#include <stdio.h>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -33,9 +34,13 @@ struct DeviceGuard {
 
 }  // namespace
 
+// text of the last HIP failure seen by the calling thread, for dz_strerror(DZ_ERR_HIP)
+static thread_local char t_hip_err[288] = "HIP runtime failure";
+
 int dz_set_hip_error(dz_ctx *ctx, hipError_t e)
 {
     if (e == hipSuccess) return DZ_OK;
+    snprintf(t_hip_err, sizeof(t_hip_err), "HIP runtime failure: %s", hipGetErrorString(e));
     if (ctx) {
         strncpy(ctx->hip_err, hipGetErrorString(e), sizeof(ctx->hip_err) - 1);
         ctx->hip_err[sizeof(ctx->hip_err) - 1] = 0;
@@ -154,7 +159,7 @@ const char *dz_strerror(int rc)
     case DZ_ERR_SHAPE: return "unsupported shape (need N % 16 == 0, K % 256 == 0, group 64 or 128)";
     case DZ_ERR_BITS: return "bits must be 2 or 4";
     case DZ_ERR_ALIGN: return "device pointer is not 16-byte aligned";
-    case DZ_ERR_HIP: return "HIP runtime failure";
+    case DZ_ERR_HIP: return t_hip_err;          // carries the runtime's own text for this thread's last failure
     case DZ_ERR_INDEX: return "a request index was outside [-1, D)";
     case DZ_ERR_LIMIT: return "the call needs more workspace than this entry point or context may use";
     default: return "unknown error";

@@ -84,6 +84,9 @@ def test_growth_during_capture_is_an_error(dz):
             ob.zero_()
             rc = dz.dz_linear(c.h, big.dx, big.dW, big.packed, big.dids, ob, 5000, 32, 256, 4, 64, check=False)
         assert rc == dz.DZ_ERR_HIP
+        msg = dz.dz_strerror(rc)                     # the runtime's own text travels with the code
+        assert msg.startswith("HIP runtime failure: ") and len(msg) > len("HIP runtime failure: "), msg
+        assert dz.lib().dz_last_hip_error(c.h).decode() in msg
         torch.cuda.synchronize()
         dz.dz_linear(c.h, big.dx, big.dW, big.packed, big.dids, ob, 5000, 32, 256, 4, 64)
         assert dz.dz_check(c.h) == dz.DZ_OK
