@@ -46,3 +46,20 @@ def test_oracle_and_product_are_independent():
     orc = imports(os.path.join(ROOT, "oracle"))
     assert "oracle" not in prod
     assert "paper_2312_05215_amd" not in orc and "libdz.so" not in orc and "csrc" not in orc
+
+
+def test_committed_traffic_summaries_are_readable_by_the_benchmark():
+    """bench.py fills roofline.traffic from profiles/<kernel>_<workload>_pmc.txt; every performance workload
+    has one, and the figure is at least the algorithmic bytes' order of magnitude."""
+    import importlib.util
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    for kernel, workload, launches in (("stream_kernel", "7b_decode", 4), ("stream_kernel", "7b_decode_many", 4),
+                                       ("stream_kernel", "70b_stack", 4), ("prefill_kernel", "13b_prefill", 7)):
+        traffic, src = bench.profile_traffic(kernel, workload, launches)
+        assert traffic is not None and traffic > 100e6, (kernel, workload, traffic)
+        assert src == os.path.join("profiles", f"{kernel}_{workload}_pmc.txt")
+        assert bench.profile_traffic(kernel, workload, launches + 1) == (None, None)      # other launch grouping: no figure
