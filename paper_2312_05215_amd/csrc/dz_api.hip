@@ -203,6 +203,7 @@ int dz_create(dz_ctx **out, int device)
         e = hipMalloc((void **)&ctx->partial, ctx->partial_bytes);
     }
     if (e != hipSuccess) {
+        (void)dz_set_hip_error(nullptr, e);     // the context goes away: keep the text for dz_strerror
         dz_destroy(ctx);
         return DZ_ERR_HIP;
     }
