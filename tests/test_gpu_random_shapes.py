@@ -74,3 +74,31 @@ def test_random_shape_through_the_streaming_kernel_at_any_batch_size(dz, i):
         c.set_option(dz.DZ_OPT_LARGE_BATCH_STREAMING, 1)
         cs = Case(dz, c.h, 2000 + i, T, N, K, D, bits, G, _ids(kind, T, D, 2000 + i))
         _run_all(dz, c, cs, tag)
+
+
+@pytest.mark.parametrize("i", range(32, 44))
+def test_random_group(dz, i):
+    """dz_linear_group on 1..4 random projections that share x and the request vector, each against the oracle."""
+    import oracle
+    r = np.random.default_rng(20231205 + i)
+    T, _, K, D, bits, G, kind = _draw(i)
+    P = int(r.integers(1, 5))
+    Ns = [16 * int(r.integers(1, 18)) for _ in range(P)]
+    D = min(D, 24)
+    while T * sum(Ns) * K > 80_000_000:
+        K = max(256, K - 256)
+        if K == 256:
+            T = max(1, T // 2)
+    tag = f"random-group[{i}] T={T} K={K} D={D} bits={bits} G={G} ids={kind} N={Ns}"
+    print(tag, flush=True)
+    with dz.Context(0) as c:
+        ids = _ids(kind, T, D, 3000 + i)
+        cases = [Case(dz, c.h, 3000 + 10 * i + p, T, N, K, D, bits, G, ids) for p, N in enumerate(Ns)]
+        first = cases[0]
+        outs = [cs.out(fill=7.0) for cs in cases]
+        dz.dz_linear_group(c.h, first.dx, [cs.dW for cs in cases], [cs.packed for cs in cases], first.dids, outs, T, Ns,
+                           K, bits, G)
+        assert dz.dz_check(c.h) == dz.DZ_OK
+        for p, cs in enumerate(cases):
+            ref = oracle.c.linear(first.x.numpy(), cs.W.numpy(), cs.dense, first.ids.numpy())
+            assert_close(outs[p], ref, f"{tag} projection {p}")
