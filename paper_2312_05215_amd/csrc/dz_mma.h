@@ -205,9 +205,9 @@ __device__ __forceinline__ void base_issue(__amdgpu_buffer_rsrc_t rw, const uint
     }
 }
 
-template <int R, int J>
+template <int R, int J, int JA = J>
 __device__ __forceinline__ void base_compute(const u32x4 (&buf)[R][2], const _Float16 *xs, const Geo &g,
-                                             const int (&brow)[J], int kofs, f4 (&acc)[R][J])
+                                             const int (&brow)[J], int kofs, f4 (&acc)[R][JA])
 {
 #pragma unroll
     for (int j = 0; j < J; ++j) {

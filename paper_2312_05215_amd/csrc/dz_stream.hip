@@ -34,65 +34,68 @@
 namespace {
 
 // ---- delta phase of the streaming kernel -------------------------------------------------------
-// A task = one packed tile (16 rows x 256 k per row tile) of one delta segment.  What a task needs
-// to know about its segment -- the blob pointer and the range [sb, se) of sorted positions -- sits
-// in registers, segment i in lane i, and is fetched with a lane read: no LDS round trip stands
-// between a task and its loads.
-struct SegTable {
-    uint32_t plo, phi;      // packed-delta blob of the segment's delta (for the current projection)
-    int sb, se;             // sorted positions [sb, se)
+// A task = one packed tile (16 rows x 256 k per row tile) of one delta segment.  The delta phase works
+// on *windows* of two column blocks (32 sorted request positions).  The B fragments of one k tile for
+// the window's column blocks and all four steps are held in registers (64 per wave) for as long as
+// that k tile's segments are multiplied: every segment's sparse MFMAs read them from there, so the
+// delta phase reads x from LDS once per k tile and window instead of once per segment.  A batch of
+// more than 32 rows has two windows; the sorted order makes the segments that overlap a window a
+// contiguous run of the segment list, so each window streams only its own segments' packed tiles (a
+// segment that straddles position 32 is streamed by both).
+//
+// The tasks of a k tile are the *entries* of the batch: window 0's segments, then window 1's.  What a
+// task needs to know about its entry sits in registers, entry e in lane e, and is fetched with a lane
+// read: no LDS round trip and no cursor arithmetic stands between a task and its loads.
+struct EntryTable {
+    uint32_t plo, phi;      // packed-delta blob of the entry's delta (for the current projection)
+    int rel;                // first sorted position of the segment, counted from the window's first position
+    int lenf;               // rows of the segment | window << 8 | (first entry of its window) << 9
 };
-
-// The delta phase works on *windows* of two column blocks (32 sorted request positions).  The B
-// fragments of one k tile for the window's column blocks and all four steps are held in registers
-// (64 per wave) for as long as that k tile's segments are multiplied: every segment's sparse MFMAs
-// read them from there, so the delta phase reads x from LDS once per k tile and window instead of
-// once per segment.  A batch of more than 32 rows has two windows; the sorted order makes the
-// segments that overlap a window a contiguous run of the segment table, so each window streams only
-// its own segments' packed tiles (a segment that straddles position 32 is streamed by both).
 constexpr int WIN = 2;              // column blocks per window
+constexpr int ENTRY_WINDOW = 0x100, ENTRY_FIRST = 0x200;
 
-template <int J, int J0, int JW>
-__device__ __forceinline__ void load_window_frags(const _Float16 *xs, const int (&brow)[J], const Geo &g, int kofs,
+template <int JW>
+__device__ __forceinline__ void load_window_frags(const _Float16 *xs, const int (&wrow)[WIN], const Geo &g, int kofs,
                                                   h16 (&bf)[4][WIN])
 {
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int j = 0; j < JW; ++j) bf[s][j] = load_b(xs, brow[J0 + j], g, kofs + s * 64);
+        for (int j = 0; j < JW; ++j) bf[s][j] = load_b(xs, wrow[j], g, kofs + s * 64);
 }
 
 template <int BITS, int GROUP, bool QO, int R>
-__device__ __forceinline__ void stream_delta_issue(const Cursor &c, bool valid, const Geo &g, const int (&rtc)[R],
-                                                   const LaneOffs &lo, const SegTable &tab, uint32_t off_idx,
+__device__ __forceinline__ void stream_delta_issue(int e, int kt, bool valid, const Geo &g, const int (&rtc)[R],
+                                                   const LaneOffs &lo, const EntryTable &tab, uint32_t off_idx,
                                                    uint32_t off_scale, uint32_t blob_bytes,
                                                    uint32_t (&st)[R][Fmt<BITS, GROUP, QO>::SD])
 {
     // With no task left the loads are still issued (so the load count never depends on a branch)
     // but against an empty resource: the hardware returns zeros and touches no memory.
-    const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)tab.plo, c.seg);
-    const uint32_t h = (uint32_t)__builtin_amdgcn_readlane((int)tab.phi, c.seg);
+    const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)tab.plo, e);
+    const uint32_t h = (uint32_t)__builtin_amdgcn_readlane((int)tab.phi, e);
     const __amdgpu_buffer_rsrc_t rs = make_rsrc((const void *)(((unsigned long long)h << 32) | l), valid ? blob_bytes : 0u);
 #pragma unroll
     for (int r = 0; r < R; ++r)
-        tile_loads<BITS, GROUP, QO>(rs, (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)c.kt, lo, off_idx, off_scale, st[r]);
+        tile_loads<BITS, GROUP, QO>(rs, (uint32_t)rtc[r] * (uint32_t)g.KT + (uint32_t)kt, lo, off_idx, off_scale, st[r]);
 }
 
-// The four steps of one packed tile (stage registers st) of the segment [sb, se) of sorted positions,
-// against the window of column blocks J0 .. J0 + JW - 1.  The sparse MFMAs multiply all request columns
-// of the window (the fragments in registers are not masked) into a copy of the accumulators; lanes
-// whose request column lies in the segment then keep the copy, the others keep what they had: one
-// select per accumulator register and task instead of a masked read of x per step.
-template <int BITS, int GROUP, bool QO, int R, int J, int J0, int JW>
-__device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BITS, GROUP, QO>::SD], int sb, int se,
-                                                  const h16 (&bf)[4][WIN], const Geo &g, f4 (&acc)[R][J])
+// The four steps of one packed tile (stage registers st) of a segment of `len` sorted positions that
+// begins at position `rel` of the current window, whose accumulators are acc[.][0 .. JW-1].  The sparse
+// MFMAs multiply all request columns of the window (the fragments in registers are not masked) into a
+// copy of the accumulators; lanes whose request column lies in the segment then keep the copy, the
+// others keep what they had: one select per accumulator register and task instead of a masked read of
+// x per step.
+template <int BITS, int GROUP, bool QO, int R, int JA, int JW>
+__device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BITS, GROUP, QO>::SD], int rel, int len,
+                                                  const h16 (&bf)[4][WIN], const Geo &g, f4 (&acc)[R][JA])
 {
     typedef Fmt<BITS, GROUP, QO> F;
     f4 tmp[R][JW];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int j = 0; j < JW; ++j) tmp[r][j] = acc[r][J0 + j];
+        for (int j = 0; j < JW; ++j) tmp[r][j] = acc[r][j];
 #pragma unroll
     for (int h = 0; h < F::NH; ++h)
 #pragma unroll
@@ -116,18 +119,33 @@ __device__ __forceinline__ void stream_delta_task(const uint32_t (&st)[R][Fmt<BI
             }
         }
     }
-    const unsigned len = (unsigned)(se - sb);
 #pragma unroll
     for (int j = 0; j < JW; ++j) {
-        const bool in = (unsigned)(16 * (J0 + j) + g.row - sb) < len;
+        const bool in = (unsigned)(16 * j + g.row - rel) < (unsigned)len;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            acc[r][J0 + j].x = in ? tmp[r][j].x : acc[r][J0 + j].x;
-            acc[r][J0 + j].y = in ? tmp[r][j].y : acc[r][J0 + j].y;
-            acc[r][J0 + j].z = in ? tmp[r][j].z : acc[r][J0 + j].z;
-            acc[r][J0 + j].w = in ? tmp[r][j].w : acc[r][J0 + j].w;
+            acc[r][j].x = in ? tmp[r][j].x : acc[r][j].x;
+            acc[r][j].y = in ? tmp[r][j].y : acc[r][j].y;
+            acc[r][j].z = in ? tmp[r][j].z : acc[r][j].z;
+            acc[r][j].w = in ? tmp[r][j].w : acc[r][j].w;
         }
     }
+}
+
+// The accumulators of the window the delta phase works on are always the first two column blocks'
+// registers: entering the other window exchanges the two halves (and leaving it exchanges them back).
+template <int R, int JA>
+__device__ __forceinline__ void swap_windows(f4 (&acc)[R][JA])
+{
+    static_assert(JA == 2 * WIN, "two windows");
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < WIN; ++j) {
+            const f4 t = acc[r][j];
+            acc[r][j] = acc[r][WIN + j];
+            acc[r][WIN + j] = t;
+        }
 }
 
 // An LDS round holds the x rows of RT2 k tiles (8 for one column block, 4 for two, 2 for three or four:
@@ -282,7 +300,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     int nseg = 0;
     // segments of the sorted order that overlap window 0 (positions 0 .. 31) and window 1 (32 .. 63)
     constexpr int NW = (J + WIN - 1) / WIN;
-    int wlo0 = 0, whi0 = 0, wlo1 = 0, whi1 = 0, ns0 = 0, ns1 = 0;
+    int wlo1 = 0, ns0 = 0, ne = 0;               // window 1's first segment; entries of window 0, of both windows
     int brow[J];
 #pragma unroll
     for (int j = 0; j < J; ++j) brow[j] = 0;
@@ -313,11 +331,15 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         rvalid[r] = rt < RT;
         rtc[r] = rvalid[r] ? rt : RT - 1;
     }
-    f4 acc[R][J];
+    // with two windows there are always four column blocks of accumulators (J = 3: the fourth is window 1's
+    // unused second block, whose request positions lie in no segment)
+    constexpr int JA = (NW > 1) ? 2 * WIN : J;
+    constexpr int JW = (J < WIN) ? J : WIN;      // column blocks a delta task multiplies
+    f4 acc[R][JA];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int j = 0; j < J; ++j) acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < JA; ++j) acc[r][j] = (f4){0.f, 0.f, 0.f, 0.f};
     for (int kr0 = kt0; kr0 < kt1; kr0 += rtiles) {
         const int kr1 = min(kt1, kr0 + rtiles);
         const int ntr = kr1 - kr0;
@@ -330,49 +352,55 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             const int nk = kr1 < kt1 ? kr1 : p - (p / g.KT) * g.KT;
             if (kr1 < kt1 || p < p_end) DZ_XDMA(xbuf ^ 1, nk);
         }
-        // Delta tasks of this round, in issue order: window 0's (k tile by k tile, all of its segments per
-        // k tile), padded to a multiple of the stage-buffer count so that window 1's start at rotation
-        // phase 0, then window 1's.  Set after the sort in round one.
-        int nd0 = ns0 * ntr, nd0p = NW > 1 ? (nd0 + DSTG - 1) / DSTG * DSTG : nd0, nd = nd0p + ns1 * ntr;
-        Cursor ci, cc;
-        ci.kt = kr0; ci.seg = wlo0;
-        cc = ci;
-        // named stage buffers, rotated by hand.  Issue cursors stop at the last task / step and
-        // re-issue it (a few redundant cache hits at the end of a segment) so that issuing needs no branch.
+        // Delta tasks of this round, in issue order: k tile by k tile, all entries per k tile (window 0's
+        // segments, then window 1's).  Set after the sort in round one.
+        int nd = ne * ntr;
+        int ie = 0, ikt = kr0;                   // issue cursor: entry and k tile of the next task to request
+        // named stage buffers, rotated by hand; entry and k tile (counted from the round's first) of the task
+        // a buffer holds travel with it in scalars of their own
         uint32_t st0[R][SD], st1[R][SD], st2[R][SD];
+        int de0 = 0, dk0 = 0, de1 = 0, dk1 = 0, de2 = 0, dk2 = 0;
         uint32_t wbase[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) wbase[r] = ((uint32_t)rtc[r] * 16u * (uint32_t)a.K + (uint32_t)kr0 * 256u) * 2u;
         int ti = 0, tc = 0;
-        // the issue cursor walks the same order two tasks ahead of the multiplying one; in the padding
-        // and past the end the loads are issued against an empty resource
-#define DZ_ISSUE(buf)                                                                                              \
+        int wcur = 0;                            // the window whose accumulators are in front
+        // the issue cursor walks the same order two tasks ahead of the multiplying one; past the end the
+        // loads are issued against an empty resource
+#define DZ_ISSUE(buf, de, dk)                                                                                      \
     do {                                                                                                           \
-        const bool live = ti < nd0 || (ti >= nd0p && ti < nd);                                                     \
-        stream_delta_issue<BITS, GROUP, QO, R>(ci, live, g, rtc, lo, tab, off_idx, off_scale, blob_bytes, buf);    \
+        stream_delta_issue<BITS, GROUP, QO, R>(ie, ikt, ti < nd, g, rtc, lo, tab, off_idx, off_scale, blob_bytes, buf); \
+        de = ie; dk = ikt - kr0;                                                                                   \
         ++ti;                                                                                                      \
-        if (NW > 1 && ti == nd0p) { ci.kt = kr0; ci.seg = wlo1; }                                                  \
-        else if (ti < nd0) advance_seg(ci, wlo0, whi0);                                                            \
-        else if (NW > 1 && ti > nd0p && ti < nd) advance_seg(ci, wlo1, whi1);                                      \
+        const int wrap_ = (ie + 1 >= ne) ? 1 : 0;                                                                  \
+        ie = wrap_ ? 0 : ie + 1;                                                                                   \
+        ikt += wrap_;                                                                                              \
     } while (0)
-#define DZ_STEP(W, cur, nxt)                                                                                       \
+#define DZ_STEP(cur, de, dk, nxt, den, dkn)                                                                        \
     do {                                                                                                           \
-        constexpr int J0 = (W) * WIN, JW = (J - J0 < WIN) ? J - J0 : WIN;                                          \
-        const int slo = (W) ? wlo1 : wlo0, shi = (W) ? whi1 : whi0;                                                \
-        DZ_ISSUE(nxt);                                                                                             \
-        if (tc < ((W) ? nd : nd0)) {                                                                               \
-            if (cc.seg == slo) load_window_frags<J, J0, JW>(xc, brow, g, (cc.kt - kr0) * 256, bf);  /* new k tile */ \
-            const int sb = __builtin_amdgcn_readlane(tab.sb, cc.seg);                                              \
-            const int se = __builtin_amdgcn_readlane(tab.se, cc.seg);                                              \
-            stream_delta_task<BITS, GROUP, QO, R, J, J0, JW>(cur, sb, se, bf, g, acc);                             \
-            advance_seg(cc, slo, shi);                                                                             \
+        DZ_ISSUE(nxt, den, dkn);                                                                                   \
+        if (tc < nd) {                                                                                             \
+            const int lenf = __builtin_amdgcn_readlane(tab.lenf, de);                                              \
+            const int rel = __builtin_amdgcn_readlane(tab.rel, de);                                                \
+            if (lenf & ENTRY_FIRST) {               /* new (window, k tile): its B fragments */                    \
+                if constexpr (NW > 1) {                                                                            \
+                    const int w_ = (lenf & ENTRY_WINDOW) ? 1 : 0;                                                  \
+                    if (w_ != wcur) { swap_windows<R, JA>(acc); wcur = w_; }                                       \
+                    const int wrow[WIN] = {w_ ? brow[WIN] : brow[0], w_ ? brow_last : brow[1]};                    \
+                    load_window_frags<JW>(xc, wrow, g, (dk) * 256, bf);                                            \
+                } else {                                                                                           \
+                    const int wrow[WIN] = {brow[0], brow[JW - 1]};                                                 \
+                    load_window_frags<JW>(xc, wrow, g, (dk) * 256, bf);                                            \
+                }                                                                                                  \
+            }                                                                                                      \
+            stream_delta_task<BITS, GROUP, QO, R, JA, JW>(cur, rel, lenf & 0xff, bf, g, acc);                      \
         }                                                                                                          \
         ++tc;                                                                                                      \
     } while (0)
 #define DZ_BSTEP(s, cur, nxt)                                                                                      \
     do {                                                                                                           \
         base_issue<R>(rw, wbase, lo.w, min((s) + BDIST, seg_last), nxt);                                           \
-        base_compute<R, J>(cur, xc, g, brow, (s) * 64, acc);                                                       \
+        base_compute<R, J, JA>(cur, xc, g, brow, (s) * 64, acc);                                                       \
     } while (0)
         if constexpr (HAS_BASE) {
             if (!w_ahead) {                      // first round of a segment: the weight loads start here and
@@ -443,34 +471,34 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             tables_ready = true;
             nseg = HAS_DELTA ? s_nseg : 0;
             if constexpr (HAS_DELTA) {
-                // the segments are in position order: those that begin below 32 come first, those that
-                // end above 32 come last
+                // the segments are in position order: those that begin below 32 come first (window 0's),
+                // those that end above 32 come last (window 1's); one that does both is an entry of both
                 const bool mine = g.lane < nseg;
                 const int sbl = mine ? s_seg_begin[g.lane] : 0, sel = mine ? s_seg_begin[g.lane + 1] : 0;
                 const unsigned long long m0 = __ballot(mine && sbl < 16 * WIN);
                 const unsigned long long m1 = __ballot(mine && sel > 16 * WIN);
-                whi0 = __builtin_popcountll(m0);
-                if (NW > 1 && m1) { wlo1 = (int)__builtin_ctzll(m1); whi1 = nseg; }
-                ns0 = whi0 - wlo0;
-                ns1 = whi1 - wlo1;
+                ns0 = __builtin_popcountll(m0);
+                ne = ns0;
+                if (NW > 1 && m1) { wlo1 = (int)__builtin_ctzll(m1); ne += __builtin_popcountll(m1); }
             }
-            nd0 = ns0 * ntr;
-            nd0p = NW > 1 ? (nd0 + DSTG - 1) / DSTG * DSTG : nd0;
-            nd = nd0p + ns1 * ntr;
-            ci.seg = cc.seg = wlo0;
+            nd = ne * ntr;
 #pragma unroll
             for (int j = 0; j < J; ++j) brow[j] = s_boff[16 * j + g.row];
             first_round = false;
         }
-        SegTable tab = {0u, 0u, 0, 0};
+        EntryTable tab = {0u, 0u, 0, 0};
         if constexpr (HAS_DELTA) {
-            if (g.lane < nseg) {                    // segment table: segment i in lane i
-                const unsigned long long bp = sd[s_seg_delta[g.lane]];
+            if (g.lane < ne) {                      // entry table: entry e in lane e
+                const int w = g.lane >= ns0 ? 1 : 0;
+                const int sg = w ? wlo1 + (g.lane - ns0) : g.lane;
+                const unsigned long long bp = sd[s_seg_delta[sg]];
+                const int sb = s_seg_begin[sg], se = s_seg_begin[sg + 1];
                 tab.plo = (uint32_t)bp; tab.phi = (uint32_t)(bp >> 32);
-                tab.sb = s_seg_begin[g.lane]; tab.se = s_seg_begin[g.lane + 1];
+                tab.rel = sb - 16 * WIN * w;
+                tab.lenf = (se - sb) | (w ? ENTRY_WINDOW : 0) | ((g.lane == 0 || g.lane == ns0) ? ENTRY_FIRST : 0);
             }
-            DZ_ISSUE(st0);
-            DZ_ISSUE(st1);
+            DZ_ISSUE(st0, de0, dk0);
+            DZ_ISSUE(st1, de1, dk1);
         }
         if constexpr (HAS_BASE) {
             for (int s = 0; s < nsteps; s += 4) {
@@ -484,18 +512,15 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         if constexpr (HAS_DELTA) {
             static_assert(DSTG == 3, "the rotation below is written for three stage buffers");
             h16 bf[4][WIN];
-            while (tc < nd0p) {
-                DZ_STEP(0, st0, st2);
-                DZ_STEP(0, st1, st0);
-                DZ_STEP(0, st2, st1);
+            // window 1's second column block does not exist with three column blocks: its lanes read zeros
+            const int brow_last = (J > WIN + 1) ? brow[J - 1] : ZROW * LDW;
+            while (tc < nd) {
+                DZ_STEP(st0, de0, dk0, st2, de2, dk2);
+                DZ_STEP(st1, de1, dk1, st0, de0, dk0);
+                DZ_STEP(st2, de2, dk2, st1, de1, dk1);
             }
             if constexpr (NW > 1) {
-                cc.kt = kr0; cc.seg = wlo1;
-                while (tc < nd) {
-                    DZ_STEP(1, st0, st2);
-                    DZ_STEP(1, st1, st0);
-                    DZ_STEP(1, st2, st1);
-                }
+                if (wcur) swap_windows<R, JA>(acc);      // the base phase and the epilogue want window 0 in front
             }
         }
 #undef DZ_ISSUE
