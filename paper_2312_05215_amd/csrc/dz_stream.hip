@@ -376,6 +376,8 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         ie = wrap_ ? 0 : ie + 1;                                                                                   \
         ikt += wrap_;                                                                                              \
     } while (0)
+        // (the empty asm statement keeps the exchange behind a real branch: as selects it would cost more
+        // than the exchange itself at every start of a window)
 #define DZ_STEP(cur, de, dk, nxt, den, dkn)                                                                        \
     do {                                                                                                           \
         DZ_ISSUE(nxt, den, dkn);                                                                                   \
@@ -385,7 +387,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
             if (lenf & ENTRY_FIRST) {               /* new (window, k tile): its B fragments */                    \
                 if constexpr (NW > 1) {                                                                            \
                     const int w_ = (lenf & ENTRY_WINDOW) ? 1 : 0;                                                  \
-                    if (w_ != wcur) { swap_windows<R, JA>(acc); wcur = w_; }                                       \
+                    if (w_ != wcur) { asm volatile("; window switch"); swap_windows<R, JA>(acc); wcur = w_; }      \
                     const int wrow[WIN] = {w_ ? brow[WIN] : brow[0], w_ ? brow_last : brow[1]};                    \
                     load_window_frags<JW>(xc, wrow, g, (dk) * 256, bf);                                            \
                 } else {                                                                                           \
