@@ -211,7 +211,8 @@ __global__ __launch_bounds__(PW * 64) void prefill_kernel(DzStreamArgs a, DzDelt
     const int slot0 = (tile - 8 * I0) * S;              // first partial-sum slot of a sliced tile
     const int rb = tile / nchunks;
     const int chunk = tile - rb * nchunks;
-    const int kb = (int)((long long)ks * g.KT / S), ke = (int)((long long)(ks + 1) * g.KT / S);   // k tiles [kb, ke)
+    const int kb = (int)((uint32_t)ks * (uint32_t)g.KT / (uint32_t)S);      // k tiles [kb, ke)
+    const int ke = (int)((uint32_t)(ks + 1) * (uint32_t)g.KT / (uint32_t)S);
     const int p0 = chunk * PCH;
     const int cnt = min(PCH, a.T - p0);
     const int RT = a.N >> 4;

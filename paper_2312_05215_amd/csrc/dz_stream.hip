@@ -203,9 +203,11 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     const int G = a.S;
     const int chunk = blockIdx.x / G;
     const int wg = blockIdx.x - chunk * G;
-    const long long P = (long long)NRB * g.KT;
-    const int p_begin = (int)((long long)wg * P / G);
-    const int p_end = (int)((long long)(wg + 1) * P / G);
+    // (32-bit arithmetic: the host keeps (P + 1) * (G + 1) below 2^31; a 64-bit division is some 150
+    // scalar instructions, and four of them stood between a workgroup and its first load)
+    const uint32_t P = (uint32_t)NRB * (uint32_t)g.KT;
+    const int p_begin = (int)((uint32_t)wg * P / (uint32_t)G);
+    const int p_end = (int)((uint32_t)(wg + 1) * P / (uint32_t)G);
     const int p0 = chunk * 64;
     const int cnt = min(64, a.T - p0);
 
@@ -216,9 +218,12 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     // the rest of the start-up -- tables, the x slice, the ranking of the batch -- runs under them.
     u32x4 bw0[R][2], bw1[R][2], bw2[R][2], bw3[R][2];
     bool w_ahead = false;
+    // row block and k tile the range starts at; the pieces that follow begin at k tile 0 of the next row block
+    int rb_next = (int)((uint32_t)p_begin / (uint32_t)g.KT);
+    int kt_next = p_begin - rb_next * g.KT;
     if (HAS_BASE && p_begin < p_end) {
-        const int rb = p_begin / g.KT;
-        const int kt0 = p_begin - rb * g.KT;
+        const int rb = rb_next;
+        const int kt0 = kt_next;
         const int steps = 4 * min(g.KT - kt0, p_end - p_begin);
         int pj = 0;
         while (pj + 1 < gp.P && rb >= gp.rb_start[pj + 1]) ++pj;
@@ -294,7 +299,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     } while (0)
     const int rtiles = (round_tiles > 0 && round_tiles < RT2) ? round_tiles : RT2;      // k tiles a round multiplies
     int xbuf = 0;                                // the buffer that holds the current round's x
-    if (p_begin < p_end) DZ_XDMA(0, p_begin - (p_begin / g.KT) * g.KT);
+    if (p_begin < p_end) DZ_XDMA(0, kt_next);
     bool tables_ready = !sort_here;
     bool first_round = true;
     int nseg = 0;
@@ -306,10 +311,11 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     for (int j = 0; j < J; ++j) brow[j] = 0;
 
   for (int p = p_begin; p < p_end;) {
-    const int rb = p / g.KT;
-    const int kt0 = p - rb * g.KT;
+    const int rb = rb_next;
+    const int kt0 = kt_next;
     const int kt1 = min(g.KT, kt0 + (p_end - p));
     p += kt1 - kt0;
+    ++rb_next; kt_next = 0;                      // a piece that is not the last ends with its row block
     // the projection this row block belongs to (a call may carry several projections that share
     // x: their row blocks are numbered one projection after the other)
     int pj = 0;
@@ -349,7 +355,7 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
         // ---- the next round's x starts its way into the other buffer (everybody left that buffer at
         // the barrier that ended the previous round)
         {
-            const int nk = kr1 < kt1 ? kr1 : p - (p / g.KT) * g.KT;
+            const int nk = kr1 < kt1 ? kr1 : 0;     // the next piece starts a row block
             if (kr1 < kt1 || p < p_end) DZ_XDMA(xbuf ^ 1, nk);
         }
         // Delta tasks of this round, in issue order: k tile by k tile, all entries per k tile (window 0's
@@ -541,8 +547,8 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     // ---- results of this segment: lane 16q + c holds rows 4q..4q+3 of the row tile for request
     // column c.  Which workgroups contribute to row block rb follows from the range formula:
     // the owner of flat position f is ceil((f + 1) * G / P) - 1.
-    const int w_first = (int)((((long long)rb * g.KT + 1) * G + P - 1) / P) - 1;
-    const int w_last = (int)((((long long)(rb + 1) * g.KT) * G + P - 1) / P) - 1;
+    const int w_first = (int)((((uint32_t)rb * (uint32_t)g.KT + 1u) * (uint32_t)G + P - 1u) / P) - 1;
+    const int w_last = (int)((((uint32_t)(rb + 1) * (uint32_t)g.KT) * (uint32_t)G + P - 1u) / P) - 1;
     const int ncontrib = w_last - w_first + 1;
     if (ncontrib == 1) {
 #pragma unroll
@@ -701,6 +707,7 @@ int dz_launch_stream(dz_ctx *ctx, const DzStreamArgs &args, const DzGroup &group
     const long long auto_wgs = (long long)cus * 8 / WAVES;
     long long G = ctx->force_splits > 0 ? (long long)ctx->force_splits * NRB : (ctx->target_wgs > 0 ? ctx->target_wgs : auto_wgs);
     if (G > P) G = P;
+    if ((P + 1) * (G + 1) >= (1ll << 31)) G = (1ll << 31) / (P + 1) - 2;      // the kernel divides in 32 bits
     if (G < 1) G = 1;
     // most workgroups that can share one row block = partial slots needed
     int max_slots = 1;

@@ -68,7 +68,8 @@ __global__ __launch_bounds__(TTHREADS) void tile_kernel(DzStreamArgs a, int NRB,
     const int slot0 = (tile - 8 * I0) * S;
     const int rb = tile / nchunks;
     const int chunk = tile - rb * nchunks;
-    const int kb = (int)((long long)ks * g.KT / S), ke = (int)((long long)(ks + 1) * g.KT / S);   // k tiles [kb, ke)
+    const int kb = (int)((uint32_t)ks * (uint32_t)g.KT / (uint32_t)S);      // k tiles [kb, ke)
+    const int ke = (int)((uint32_t)(ks + 1) * (uint32_t)g.KT / (uint32_t)S);
     const int p0 = chunk * TCH;
     const int RT = a.N >> 4;
 
