@@ -284,17 +284,26 @@ void stream_kernel(DzStreamArgs a, DzGroup gp, DzGroupPtrs dp, int NRB, int roun
     // moving 16 bytes to LDS byte 16 l of the unit.  A row without a request, and the columns past the
     // end of a row, get an offset beyond the resource: the hardware touches no memory for them (what
     // lands in LDS there is never read: such columns belong to no k tile, such rows to no column slot).
+    // The per-lane offsets of a wave's units never change (the rows are fixed once the request order is
+    // known), so they are worked out once: a load then costs a handful of scalar instructions.
+    uint32_t xvo[XNI];
+#pragma unroll
+    for (int i = 0; i < XNI; ++i) {
+        const int row = (wave * XNI + i) / (RT2 / 2);
+        const int tok = sort_here ? (row < cnt ? row : -1) : s_tok[row];
+        xvo[i] = tok >= 0 ? (uint32_t)tok * (uint32_t)a.K * 2u + (uint32_t)g.lane * 16u : 0xFFFFFFF0u;
+    }
+    const bool upper_half = g.lane >= 32;        // lanes that move the second k tile of a unit
 #define DZ_XDMA(bufi, kr)                                                                                          \
     do {                                                                                                           \
         _Pragma("unroll") for (int i = 0; i < XNI; ++i) {                                                         \
             const int u = wave * XNI + i;                                                                          \
             const int row = u / (RT2 / 2), piece = u % (RT2 / 2);                                                  \
-            const int tok = sort_here ? (row < cnt ? row : -1) : s_tok[row];                                       \
-            const int kcol = ((kr) + 2 * piece) * 256 + g.lane * 8;                                                \
-            const uint32_t vo = (tok >= 0 && kcol < a.K) ? (uint32_t)tok * (uint32_t)a.K * 2u + (uint32_t)g.lane * 16u \
-                                                         : 0xFFFFFFF0u;                                            \
+            const int k0 = (kr) + 2 * piece;        /* the unit's k tiles are k0 and k0 + 1 */                     \
+            const bool past = k0 >= g.KT || (upper_half && k0 + 1 >= g.KT);                                        \
+            const uint32_t vo = past ? 0xFFFFFFF0u : xvo[i];                                                       \
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void *)(xs + (bufi) * BUFH + row * LDW + piece * 512), 16, vo, \
-                                                     (uint32_t)((kr) + 2 * piece) * 512u, 0, 0);                   \
+                                                     (uint32_t)k0 * 512u, 0, 0);                                   \
         }                                                                                                          \
     } while (0)
     const int rtiles = (round_tiles > 0 && round_tiles < RT2) ? round_tiles : RT2;      // k tiles a round multiplies
