@@ -7,17 +7,20 @@
 // organised around streaming those bytes exactly once with 16-byte loads per lane, and keeping
 // everything else (x, dequantisation, 2:4 expansion, the merge of base and delta results) on chip:
 //
-//   * a workgroup (8 or 4 waves) owns a block of WAVES*R row tiles (16 rows each) and one slice of
-//     k; its slice of x sits in LDS and is the B operand of every MFMA; request rows are the MFMA
-//     N dimension, 16 per column block, in delta-sorted order;
+//   * a workgroup of 8 waves owns, one after the other, the pieces of a contiguous range of the
+//     (row block, k tile) grid; a wave owns one row tile (16 rows) of the row block at hand.  The
+//     workgroup's slice of x sits in LDS (two buffers filled by buffer loads with an LDS destination)
+//     and is the B operand of every MFMA; request rows are the MFMA N dimension, 16 per column block,
+//     in delta-sorted order;
 //   * base: W fragments go from global memory straight into the A operand of
 //     V_MFMA_F32_16X16X32_F16 (lane 16q+r holds W[r][8q..8q+7], one 16-byte load);
 //   * deltas: for each delta that has requests in the batch (segments of the sorted order; deltas
 //     nobody asked for are never touched) the packed tile is loaded, codes are turned into fp16
 //     pairs with a mask-or into the mantissa of 1024.0 and one packed fma, scaled, and fed with
 //     the stored 2-bit positions to V_SMFMAC_F32_16X16X64_F16, the 2:4 sparse MFMA -- the sparse
-//     expansion costs no instruction.  Lanes whose request row is not in the segment read an
-//     all-zero LDS row, so the delta product accumulates straight into the base accumulators;
+//     expansion costs no instruction.  The product covers a window of two column blocks whose B
+//     fragments stay in registers for all segments of a k tile; a per-lane select keeps it only for
+//     the request columns of the segment;
 //   * split-k partial sums meet in fp32: every workgroup stores its partial tile, the last one to
 //     arrive for a row block (an arrival counter) adds them in fixed order and rounds to fp16
 //     once.  With one slice the result is rounded and stored directly;
